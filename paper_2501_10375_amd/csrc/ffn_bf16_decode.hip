@@ -1,0 +1,297 @@
+// Expert FFN for decode-size calls (a handful of tokens), bf16 storage.
+//
+// With the experts resident in HBM, a decode step of the MoE layer is a weight
+// stream: each selected expert's three matrices are read once and multiplied
+// by a few hidden states (the paper's Table I discussion: expert parameters
+// dwarf the activations by four orders of magnitude).  These two kernels are
+// therefore organised around the HBM stream, not around the arithmetic:
+//
+//   * no permutation and no LDS staging of weights: every weight byte is used
+//     by exactly one wavefront, so it is loaded straight into MFMA operand
+//     registers with 16-byte loads (16 rows x 64 contiguous bytes per load);
+//   * the tokens of an expert form the 16 columns of a v_mfma_f32_16x16x32_bf16,
+//     so up to 16 tokens share one pass over the weights; lanes whose column
+//     has no token issue no load;
+//   * each wavefront keeps P steps of loads in flight in a rotating register
+//     window (software pipeline unrolled P times) that runs across tile
+//     boundaries, so the stream never drains;
+//   * the 8 wavefronts of a workgroup split K, and their partial 16 x 16 tiles
+//     are summed through LDS in a fixed order (deterministic);
+//   * the token groups are rebuilt by every workgroup from topk_idx (at most
+//     128 integers), which is cheaper than another kernel launch.
+//
+//   dec_gemm1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f])   a = t*k + j, e = idx[a]
+//   dec_gemm2: y[t, h]   = sum over the token's experts (ascending expert id) of
+//                          w[a] * (act[a] . w2[e, h]),  fp32, one rounding to bf16
+#include "moe_internal.h"
+
+namespace moe {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int kWaves = 8;
+constexpr int kThreads = kWaves * 64;
+constexpr int kMaxTok = kDecodeMaxTokens;  // 16 = columns of one MFMA
+
+struct Groups {
+    int n_active;
+    int expert[64];         // active experts, ascending id
+    int cnt[64];            // tokens of that expert (<= 16)
+    int assign[64][kMaxTok];  // their assignment ids t*k + j, ascending
+};
+
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Builds the per-expert token lists; call with all threads, ends with a barrier.
+__device__ void build_groups(Groups& g, const int32_t* __restrict__ idx, int A, int E) {
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        int c = 0;
+        if (tid < E) {
+            for (int a = 0; a < A; ++a) {
+                const int e = min(max(idx[a], 0), E - 1);
+                if (e == tid && c < kMaxTok) ++c;
+            }
+        }
+        const uint64_t present = __ballot(c > 0);
+        const int ord = __popcll(present & ((1ull << tid) - 1ull));
+        if (tid == 0) g.n_active = __popcll(present);
+        if (c > 0) {
+            g.expert[ord] = tid;
+            g.cnt[ord] = c;
+            int n = 0;
+            for (int a = 0; a < A; ++a) {
+                const int e = min(max(idx[a], 0), E - 1);
+                if (e == tid && n < kMaxTok) g.assign[ord][n++] = a;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+__device__ inline bf16x8 load_frag(const uint16_t* p, bool on) {
+    bf16x8 v;
+    if (on) {
+        v = *reinterpret_cast<const bf16x8*>(p);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (__bf16)0.f;
+    }
+    return v;
+}
+
+template <int P>
+__global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict__ x,
+                                                       const int32_t* __restrict__ idx,
+                                                       const uint16_t* __restrict__ w1,
+                                                       const uint16_t* __restrict__ w3, int T, int k, int E, int H,
+                                                       int F, uint16_t* __restrict__ act) {
+    __shared__ Groups g;
+    __shared__ f32x4 red[2][kWaves][2][64];
+    build_groups(g, idx, T * k, E);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 15, kq = lane >> 4;
+
+    const int tiles_per_expert = F / 16;
+    const int total_tiles = g.n_active * tiles_per_expert;
+    const int tiles_per_wg = (total_tiles + gridDim.x - 1) / gridDim.x;
+    const int t0 = blockIdx.x * tiles_per_wg;
+    const int t1 = min(total_tiles, t0 + tiles_per_wg);
+    if (t0 >= t1) return;
+
+    // K split: 32-element steps dealt to the wavefronts in contiguous runs.
+    const int k_steps = H / 32;
+    const int per = (k_steps + kWaves - 1) / kWaves;
+    const int s_begin = wave * per;
+    const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
+    const int spt = (per + P - 1) / P * P;  // steps per tile, padded to the pipeline depth
+    const long total_q = (long)(t1 - t0) * spt;
+
+    bf16x8 fw1[P], fw3[P], fx[P];
+    // Issue-side state: the next step to request and the row bases of its tile.
+    int is = 0, itile = t0;
+    size_t wbase = 0, xbase = 0;
+    bool xcol = false;
+    auto enter_tile = [&]() {
+        const int d = itile / tiles_per_expert;
+        const int f0 = (itile - d * tiles_per_expert) * 16;
+        const size_t koff = (size_t)s_begin * 32 + kq * 8;
+        wbase = ((size_t)g.expert[d] * F + f0 + col) * H + koff;
+        xcol = col < g.cnt[d];
+        xbase = (size_t)(xcol ? g.assign[d][col] / k : 0) * H + koff;
+    };
+    enter_tile();
+    auto issue = [&](int i) {
+        const bool on = is < n_valid;
+        fw1[i] = load_frag(w1 + wbase + is * 32, on);
+        fw3[i] = load_frag(w3 + wbase + is * 32, on);
+        fx[i] = load_frag(x + xbase + is * 32, on && xcol);
+        if (++is == spt) {
+            is = 0;
+            if (++itile < t1) enter_tile();
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < P; ++i) issue(i);  // total_q >= spt >= P
+
+    f32x4 accg = {0.f, 0.f, 0.f, 0.f}, accu = {0.f, 0.f, 0.f, 0.f};
+    int cs = 0, ctile = t0;
+    for (long q = 0; q < total_q; q += P) {
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            accg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw1[i], fx[i], accg, 0, 0, 0);
+            accu = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw3[i], fx[i], accu, 0, 0, 0);
+            if (q + P + i < total_q) issue(i);
+        }
+        cs += P;
+        if (cs == spt) {
+            // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
+            // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
+            const int par = (ctile - t0) & 1;
+            red[par][wave][0][lane] = accg;
+            red[par][wave][1][lane] = accu;
+            __syncthreads();
+            if (tid < 256) {
+                const int p = tid & 63, r = tid >> 6;
+                const int d = ctile / tiles_per_expert;
+                const int f0 = (ctile - d * tiles_per_expert) * 16;
+                const int c = p & 15;
+                if (c < g.cnt[d]) {
+                    float gs = 0.f, us = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        gs += red[par][w][0][p][r];
+                        us += red[par][w][1][p][r];
+                    }
+                    const float v = gs / (1.f + __expf(-gs)) * us;
+                    act[(size_t)g.assign[d][c] * F + f0 + 4 * (p >> 4) + r] = f32_to_bf16_rne(v);
+                }
+            }
+            accg = f32x4{0.f, 0.f, 0.f, 0.f};
+            accu = f32x4{0.f, 0.f, 0.f, 0.f};
+            cs = 0;
+            ++ctile;
+        }
+    }
+}
+
+template <int P>
+__global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict__ act,
+                                                       const int32_t* __restrict__ idx,
+                                                       const float* __restrict__ topk_w,
+                                                       const uint16_t* __restrict__ w2, int T, int k, int E, int H,
+                                                       int F, uint16_t* __restrict__ y) {
+    __shared__ Groups g;
+    __shared__ f32x4 red[2][kWaves][64];
+    __shared__ float yacc[kMaxTok][16];
+    build_groups(g, idx, T * k, E);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 15, kq = lane >> 4;
+    const int h0 = blockIdx.x * 16;
+    if (tid < kMaxTok * 16) yacc[tid >> 4][tid & 15] = 0.f;
+
+    const int k_steps = F / 32;
+    const int per = (k_steps + kWaves - 1) / kWaves;
+    const int s_begin = wave * per;
+    const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
+    const int spt = (per + P - 1) / P * P;
+    const int D = g.n_active;
+    const long total_q = (long)D * spt;
+
+    bf16x8 fw[P], fa[P];
+    int is = 0, id = 0;
+    size_t wbase = 0, abase = 0;
+    bool acol = false;
+    auto enter_expert = [&]() {
+        const size_t koff = (size_t)s_begin * 32 + kq * 8;
+        wbase = ((size_t)g.expert[id] * H + h0 + col) * F + koff;
+        acol = col < g.cnt[id];
+        abase = (size_t)(acol ? g.assign[id][col] : 0) * F + koff;
+    };
+    if (D > 0) enter_expert();
+    auto issue = [&](int i) {
+        const bool on = is < n_valid;
+        fw[i] = load_frag(w2 + wbase + is * 32, on);
+        fa[i] = load_frag(act + abase + is * 32, on && acol);
+        if (++is == spt) {
+            is = 0;
+            if (++id < D) enter_expert();
+        }
+    };
+    if (D > 0) {
+#pragma unroll
+        for (int i = 0; i < P; ++i) issue(i);
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    int cs = 0, cd = 0;
+    for (long q = 0; q < total_q; q += P) {
+#pragma unroll
+        for (int i = 0; i < P; ++i) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[i], acc, 0, 0, 0);
+            if (q + P + i < total_q) issue(i);
+        }
+        cs += P;
+        if (cs == spt) {
+            const int par = cd & 1;
+            red[par][wave][lane] = acc;
+            __syncthreads();
+            if (tid < 256) {
+                const int p = tid & 63, r = tid >> 6;
+                const int c = p & 15;
+                if (c < g.cnt[cd]) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) s += red[par][w][p][r];
+                    const int a = g.assign[cd][c];
+                    yacc[a / k][4 * (p >> 4) + r] += topk_w[a] * s;
+                }
+            }
+            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            cs = 0;
+            ++cd;
+        }
+    }
+    __syncthreads();
+    if (tid < T * 16) {
+        const int t = tid >> 4, r = tid & 15;
+        y[(size_t)t * H + h0 + r] = f32_to_bf16_rne(yacc[t][r]);
+    }
+}
+
+int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+}  // namespace
+
+hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* x, const int32_t* topk_idx,
+                                  const float* topk_w, const void* w1, const void* w3, const void* w2, void* y,
+                                  void* act, hipStream_t stream) {
+    const int max_tiles = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
+    const int grid1 = min(compute_units(), max_tiles);
+    dec_gemm1<8><<<grid1, kThreads, 0, stream>>>(static_cast<const uint16_t*>(x), topk_idx,
+                                                 static_cast<const uint16_t*>(w1), static_cast<const uint16_t*>(w3),
+                                                 tokens, s.top_k, s.n_experts, s.hidden, s.ffn,
+                                                 static_cast<uint16_t*>(act));
+    dec_gemm2<16><<<s.hidden / 16, kThreads, 0, stream>>>(static_cast<const uint16_t*>(act), topk_idx, topk_w,
+                                                          static_cast<const uint16_t*>(w2), tokens, s.top_k,
+                                                          s.n_experts, s.hidden, s.ffn, static_cast<uint16_t*>(y));
+    return hipGetLastError();
+}
+
+}  // namespace moe

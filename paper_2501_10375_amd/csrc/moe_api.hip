@@ -1,0 +1,243 @@
+// C ABI of libmoe_hip.so: argument validation on the host, then kernel launches
+// on the caller's stream.  See include/moe.h for the contract of each call.
+#include "moe_internal.h"
+
+namespace moe {
+
+static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
+    WorkspaceLayout L{};
+    const size_t nb = (size_t)route_blocks(tokens > 0 ? tokens : 1);
+    const size_t A = (size_t)(tokens > 0 ? tokens : 1) * (size_t)s.top_k;
+    const size_t esz = s.dtype == MOE_F32 ? 4 : 2;
+    size_t off = 0;
+    L.hist = off;        off = align_up(off + nb * s.n_experts * sizeof(int32_t));
+    L.hist_next = off;   off = align_up(off + nb * s.n_experts * sizeof(int32_t));
+    L.offs = off;        off = align_up(off + (size_t)(s.n_experts + 1) * sizeof(int32_t));
+    L.row_of_slot = off; off = align_up(off + A * sizeof(int32_t));
+    L.slot_of = off;     off = align_up(off + A * sizeof(int32_t));
+    L.route_end = off;
+    L.act = off;         off = align_up(off + A * (size_t)s.ffn * esz);
+    L.out = off;         off = align_up(off + A * (size_t)s.hidden * sizeof(float));
+    L.total = off;
+    return L;
+}
+
+namespace {
+
+constexpr int kMaxTokens = 1 << 20;
+
+int check_shape(const moe_shape_t* s) {
+    if (s == nullptr) return MOE_ERR_NULL;
+    if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_DTYPE;
+    if (s->reserved != 0) return MOE_ERR_SHAPE;
+    if (s->hidden <= 0 || s->ffn <= 0 || s->hidden % 64 != 0 || s->ffn % 64 != 0) return MOE_ERR_SHAPE;
+    if (s->n_experts < 1 || s->n_experts > 64) return MOE_ERR_SHAPE;
+    if (s->top_k < 1 || s->top_k > 8 || s->top_k > s->n_experts) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Returns MOE_ERR_NULL / MOE_ERR_ALIGN for a list of required pointers.
+template <size_t N>
+int check_required(const void* const (&ptrs)[N]) {
+    for (const void* p : ptrs)
+        if (p == nullptr) return MOE_ERR_NULL;
+    for (const void* p : ptrs)
+        if (misaligned(p)) return MOE_ERR_ALIGN;
+    return MOE_OK;
+}
+
+template <size_t N>
+int check_optional(const void* const (&ptrs)[N]) {
+    for (const void* p : ptrs)
+        if (p != nullptr && misaligned(p)) return MOE_ERR_ALIGN;
+    return MOE_OK;
+}
+
+int dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
+
+bool decode_path(const moe_shape_t& s, int tokens) { return s.dtype == MOE_BF16 && tokens <= kDecodeMaxTokens; }
+
+struct Ws {
+    int32_t *hist, *hist_next, *offs, *row_of_slot, *slot_of;
+    void* act;
+    float* out;
+};
+
+Ws carve(void* workspace, const WorkspaceLayout& L) {
+    char* b = static_cast<char*>(workspace);
+    Ws w;
+    w.hist = reinterpret_cast<int32_t*>(b + L.hist);
+    w.hist_next = reinterpret_cast<int32_t*>(b + L.hist_next);
+    w.offs = reinterpret_cast<int32_t*>(b + L.offs);
+    w.row_of_slot = reinterpret_cast<int32_t*>(b + L.row_of_slot);
+    w.slot_of = reinterpret_cast<int32_t*>(b + L.slot_of);
+    w.act = b + L.act;
+    w.out = reinterpret_cast<float*>(b + L.out);
+    return w;
+}
+
+// Routing for one or two gates.  With `permute`, also leaves offs / row_of_slot / slot_of in
+// the workspace for the grouped GEMMs.
+hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* gates, int n_gates, int32_t* counts,
+                     int accumulate, int32_t* counts_next, bool permute, const Ws& ws, hipStream_t stream) {
+    if (!permute && tokens <= kDecodeMaxTokens) {
+        return launch_route_small(s, tokens, x, gates, n_gates, counts, accumulate, counts_next, stream);
+    }
+    gates[0].hist = ws.hist;
+    if (n_gates > 1) gates[1].hist = counts_next != nullptr ? ws.hist_next : nullptr;
+    hipError_t e = launch_route(s, tokens, x, gates, n_gates, stream);
+    if (e != hipSuccess) return e;
+    e = launch_finalize(s, tokens, ws.hist, gates[0].idx, counts, accumulate, permute ? ws.offs : nullptr,
+                        permute ? ws.row_of_slot : nullptr, permute ? ws.slot_of : nullptr, stream);
+    if (e != hipSuccess) return e;
+    if (n_gates > 1 && counts_next != nullptr)
+        e = launch_finalize(s, tokens, ws.hist_next, gates[1].idx, counts_next, 0, nullptr, nullptr, nullptr, stream);
+    return e;
+}
+
+hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_t* idx, const float* w,
+                   const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream) {
+    if (decode_path(s, tokens)) return launch_ffn_bf16_decode(s, tokens, x, idx, w, w1, w3, w2, y, ws.act, stream);
+    if (s.dtype == MOE_F32)
+        return launch_ffn_f32(s, tokens, static_cast<const float*>(x), w, static_cast<const float*>(w1),
+                              static_cast<const float*>(w3), static_cast<const float*>(w2), static_cast<float*>(y),
+                              ws.offs, ws.row_of_slot, ws.slot_of, static_cast<float*>(ws.act), ws.out, stream);
+    return launch_ffn_bf16(s, tokens, x, w, w1, w3, w2, y, ws.offs, ws.row_of_slot, ws.slot_of, ws.act, ws.out,
+                           stream);
+}
+
+}  // namespace
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_NULL: return "a required pointer is NULL";
+        case MOE_ERR_SHAPE: return "a dimension is outside the supported limits";
+        case MOE_ERR_DTYPE: return "unsupported dtype";
+        case MOE_ERR_WORKSPACE: return "workspace too small";
+        case MOE_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case MOE_ERR_DEVICE: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int moe_workspace_bytes(const moe_shape_t* shape, int32_t max_tokens, size_t* out_bytes) {
+    if (out_bytes == nullptr) return MOE_ERR_NULL;
+    if (int rc = check_shape(shape)) return rc;
+    if (max_tokens < 0 || max_tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    *out_bytes = workspace_layout(*shape, max_tokens).total;
+    return MOE_OK;
+}
+
+int moe_route_workspace_bytes(const moe_shape_t* shape, int32_t max_tokens, size_t* out_bytes) {
+    if (out_bytes == nullptr) return MOE_ERR_NULL;
+    if (int rc = check_shape(shape)) return rc;
+    if (max_tokens < 0 || max_tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    *out_bytes = workspace_layout(*shape, max_tokens).route_end;
+    return MOE_OK;
+}
+
+int moe_route(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate, const float* gate_bias,
+              int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t accumulate, void* workspace,
+              size_t workspace_bytes, void* hip_stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    const void* const req[] = {w_gate, counts, workspace};
+    if (int rc = check_required(req)) return rc;
+    const void* const per_token[] = {x, topk_idx, topk_w};
+    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
+    const void* const opt[] = {gate_bias};
+    if (int rc = check_optional(opt)) return rc;
+    const WorkspaceLayout L = workspace_layout(*shape, tokens);
+    if (workspace_bytes < L.route_end) return MOE_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Ws ws = carve(workspace, L);
+    if (tokens == 0)
+        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, stream));
+    GateArgs g[1] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}};
+    return dev(run_route(*shape, tokens, x, g, 1, counts, accumulate, nullptr, false, ws, stream));
+}
+
+int moe_predict_next(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate_next,
+                     const float* gate_bias_next, int32_t* pred_idx, float* pred_w, int32_t* pred_counts,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    const void* const req[] = {w_gate_next, workspace};
+    if (int rc = check_required(req)) return rc;
+    const void* const per_token[] = {x, pred_idx};
+    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
+    const void* const opt[] = {gate_bias_next, pred_w, pred_counts};
+    if (int rc = check_optional(opt)) return rc;
+    const WorkspaceLayout L = workspace_layout(*shape, tokens);
+    if (workspace_bytes < L.route_end) return MOE_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Ws ws = carve(workspace, L);
+    if (tokens == 0) {
+        if (pred_counts == nullptr) return MOE_OK;
+        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, pred_counts, 0, nullptr, nullptr, nullptr, stream));
+    }
+    GateArgs g[1] = {{w_gate_next, gate_bias_next, pred_idx, pred_w, nullptr}};
+    return dev(run_route(*shape, tokens, x, g, 1, pred_counts, 0, nullptr, false, ws, stream));
+}
+
+int moe_expert_ffn(const moe_shape_t* shape, int32_t tokens, const void* x, const int32_t* topk_idx,
+                   const float* topk_w, const void* w1, const void* w3, const void* w2, void* y, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    const void* const req[] = {w1, w3, w2, workspace};
+    if (int rc = check_required(req)) return rc;
+    const void* const per_token[] = {x, topk_idx, topk_w, y};
+    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
+    const WorkspaceLayout L = workspace_layout(*shape, tokens);
+    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    if (tokens == 0) return MOE_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Ws ws = carve(workspace, L);
+    if (!decode_path(*shape, tokens)) {
+        hipError_t e = launch_hist_from_idx(*shape, tokens, topk_idx, ws.hist, stream);
+        if (e != hipSuccess) return MOE_ERR_DEVICE;
+        e = launch_finalize(*shape, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, stream);
+        if (e != hipSuccess) return MOE_ERR_DEVICE;
+    }
+    return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+}
+
+int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate, const float* gate_bias,
+              const void* w_gate_next, const float* gate_bias_next, const void* w1, const void* w3, const void* w2,
+              void* y, int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t accumulate, int32_t* pred_idx,
+              void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    const void* const req[] = {w_gate, w1, w3, w2, counts, workspace};
+    if (int rc = check_required(req)) return rc;
+    const void* const per_token[] = {x, y, topk_idx, topk_w};
+    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
+    if (tokens > 0 && w_gate_next != nullptr && pred_idx == nullptr) return MOE_ERR_NULL;
+    const void* const opt[] = {gate_bias, w_gate_next, gate_bias_next, pred_idx};
+    if (int rc = check_optional(opt)) return rc;
+    const WorkspaceLayout L = workspace_layout(*shape, tokens);
+    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Ws ws = carve(workspace, L);
+    if (tokens == 0)
+        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, stream));
+    GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
+    const int n_gates = w_gate_next != nullptr ? 2 : 1;
+    hipError_t e = run_route(*shape, tokens, x, g, n_gates, counts, accumulate, nullptr, !decode_path(*shape, tokens), ws,
+                             stream);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Internal declarations shared by the HIP translation units of libmoe_hip.so.
+// Nothing here is part of the public ABI (see include/moe.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+// Tokens handled by one workgroup of the routing / histogram / permute kernels.
+constexpr int kRouteTokensPerBlock = 16;
+// Calls with at most this many tokens take the decode path: one fused routing
+// kernel and two weight-streaming kernels that group tokens per expert on the
+// fly, without a permutation in the workspace.
+constexpr int kDecodeMaxTokens = 32;
+
+// Rows (tokens) per M-tile of the grouped GEMMs; an M-tile never spans two experts.
+constexpr int kTileTokensF32 = 64;
+constexpr int kTileTokensBf16 = 128;
+
+struct WorkspaceLayout {
+    size_t hist;         // int32 [n_blocks, E]  per-block selection histogram
+    size_t hist_next;    // int32 [n_blocks, E]  same for the next-layer gate
+    size_t offs;         // int32 [E + 1]        exclusive scan of counts
+    size_t row_of_slot;  // int32 [A]            slot -> assignment index t*k + j
+    size_t slot_of;      // int32 [A]            assignment index -> slot
+    size_t route_end;    // bytes needed by routing-only calls
+    size_t act;          // dtype [A, F]         silu(W1 x) * (W3 x)
+    size_t out;          // fp32  [A, H]         per-assignment expert output
+    size_t total;        // bytes needed by the whole layer
+};
+
+WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens);
+
+inline int route_blocks(int tokens) {
+    return (tokens + kRouteTokensPerBlock - 1) / kRouteTokensPerBlock;
+}
+
+// One gate evaluated by the routing kernel.
+struct GateArgs {
+    const void* w;     // [E, H]
+    const float* bias; // [E] or null
+    int32_t* idx;      // [T, k]
+    float* wts;        // [T, k] or null
+    int32_t* hist;     // [n_blocks, E] or null
+};
+
+// ---- launchers (each returns hipGetLastError() after enqueueing) ----------
+
+// Gate GEMM + softmax + top-k for up to two gates that share x.  Per-block
+// histograms go to gate.hist.
+hipError_t launch_route(const moe_shape_t& s, int tokens, const void* x, const GateArgs* gates,
+                        int n_gates, hipStream_t stream);
+
+// Per-block histogram of caller-provided indices (moe_expert_ffn entry).
+hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t* idx, int32_t* hist,
+                                hipStream_t stream);
+
+// Sum block histograms into counts (counts may be null), and when
+// row_of_slot/slot_of are given build offs and the stable token->expert
+// permutation.
+hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
+                           int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
+                           int32_t* slot_of, hipStream_t stream);
+
+// Decode path (tokens <= kDecodeMaxTokens): routing for up to two gates with
+// counts written directly, in one workgroup.
+hipError_t launch_route_small(const moe_shape_t& s, int tokens, const void* x, const GateArgs* gates,
+                              int n_gates, int32_t* counts, int accumulate, int32_t* counts_next,
+                              hipStream_t stream);
+
+// Grouped expert FFN, fp32 storage.
+hipError_t launch_ffn_f32(const moe_shape_t& s, int tokens, const float* x, const float* topk_w,
+                          const float* w1, const float* w3, const float* w2, float* y,
+                          const int32_t* offs, const int32_t* row_of_slot, const int32_t* slot_of,
+                          float* act, float* out, hipStream_t stream);
+
+// Grouped expert FFN, bf16 storage, MFMA (prefill-size calls).
+hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w,
+                           const void* w1, const void* w3, const void* w2, void* y,
+                           const int32_t* offs, const int32_t* row_of_slot, const int32_t* slot_of,
+                           void* act, float* out, hipStream_t stream);
+
+// Weight-streaming expert FFN, bf16 storage (tokens <= kDecodeMaxTokens).
+hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* x,
+                                  const int32_t* topk_idx, const float* topk_w, const void* w1,
+                                  const void* w3, const void* w2, void* y, void* act,
+                                  hipStream_t stream);
+
+}  // namespace moe

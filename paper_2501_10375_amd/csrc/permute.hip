@@ -1,0 +1,111 @@
+// Expert activation counts and the token -> expert permutation.
+//
+// The counts are the per-sequence "activity level" of each expert that DAOP's
+// sequence-specific allocation consumes (Sec. IV-B, Algorithm 1: tokens
+// assigned to each expert).  The permutation groups the (token, j) selections
+// by expert so that each expert processes all of its tokens together
+// (Algorithm 1's parallel local expert execution).
+//
+// Everything is integer work and fully deterministic: each workgroup of the
+// routing kernel leaves a histogram of its 16 tokens; here every workgroup
+// re-derives, from those histograms, the expert totals and the number of
+// selections that precede its own tokens, then ranks its own selections in
+// token order.  The resulting order inside an expert is by (token, j).
+#include "moe_internal.h"
+
+namespace moe {
+namespace {
+
+__global__ __launch_bounds__(64) void hist_from_idx_kernel(const int32_t* __restrict__ idx, int tokens, int k,
+                                                           int E, int32_t* __restrict__ hist) {
+    __shared__ int h[64];
+    const int tid = threadIdx.x;
+    h[tid] = 0;
+    __syncthreads();
+    const int a0 = blockIdx.x * kRouteTokensPerBlock * k;
+    const int a1 = min(tokens * k, a0 + kRouteTokensPerBlock * k);
+    for (int a = a0 + tid; a < a1; a += 64) {
+        const int e = min(max(idx[a], 0), E - 1);
+        atomicAdd(&h[e], 1);
+    }
+    __syncthreads();
+    if (tid < E) hist[(size_t)blockIdx.x * E + tid] = h[tid];
+}
+
+// grid = max(1, n_blocks) workgroups of 256 threads.
+__global__ __launch_bounds__(256) void finalize_kernel(const int32_t* __restrict__ hist, int n_blocks, int E,
+                                                       int k, int tokens, const int32_t* __restrict__ idx,
+                                                       int32_t* __restrict__ counts, int accumulate,
+                                                       int32_t* __restrict__ offs,
+                                                       int32_t* __restrict__ row_of_slot,
+                                                       int32_t* __restrict__ slot_of) {
+    __shared__ int total[64];
+    __shared__ int before[64];
+    __shared__ int base[64];
+    __shared__ int local_e[kRouteTokensPerBlock * 8];
+    const int tid = threadIdx.x;
+    const int blk = blockIdx.x;
+    if (tid < 64) {
+        total[tid] = 0;
+        before[tid] = 0;
+    }
+    __syncthreads();
+    {
+        const int e = tid & 63, part = tid >> 6;
+        if (e < E) {
+            int tot = 0, bef = 0;
+            for (int b = part; b < n_blocks; b += 4) {
+                const int v = hist[(size_t)b * E + e];
+                tot += v;
+                if (b < blk) bef += v;
+            }
+            atomicAdd(&total[e], tot);
+            atomicAdd(&before[e], bef);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            base[e] = run + before[e];
+            if (blk == 0 && offs != nullptr) offs[e] = run;
+            run += total[e];
+        }
+        if (blk == 0 && offs != nullptr) offs[E] = run;
+    }
+    if (blk == 0 && counts != nullptr && tid < E) counts[tid] = (accumulate ? counts[tid] : 0) + total[tid];
+    if (row_of_slot == nullptr) return;
+    const int a0 = blk * kRouteTokensPerBlock * k;
+    const int n_local = min(tokens * k, a0 + kRouteTokensPerBlock * k) - a0;
+    if (tid < n_local) local_e[tid] = min(max(idx[a0 + tid], 0), E - 1);
+    __syncthreads();
+    if (tid < n_local) {
+        const int e = local_e[tid];
+        int rank = 0;
+        for (int i = 0; i < tid; ++i) rank += (local_e[i] == e);
+        const int slot = base[e] + rank;
+        slot_of[a0 + tid] = slot;
+        row_of_slot[slot] = a0 + tid;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t* idx, int32_t* hist,
+                                hipStream_t stream) {
+    const int nb = route_blocks(tokens);
+    if (nb > 0) hist_from_idx_kernel<<<nb, 64, 0, stream>>>(idx, tokens, s.top_k, s.n_experts, hist);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
+                           int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
+                           int32_t* slot_of, hipStream_t stream) {
+    const int nb = route_blocks(tokens);
+    const int grid = (row_of_slot != nullptr && nb > 0) ? nb : 1;
+    finalize_kernel<<<grid, 256, 0, stream>>>(hist, nb, s.n_experts, s.top_k, tokens, idx, counts, accumulate,
+                                              offs, row_of_slot, slot_of);
+    return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,191 @@
+"""Thin ctypes binding of libmoe_hip.so (see include/moe.h for the contract).
+
+Argument marshalling only: every function here takes torch tensors that live on
+the GPU, checks dtypes/shapes, passes their device pointers and the current HIP
+stream to the C entry point of the same name, and raises on a non-zero status.
+No step of the MoE layer is computed in Python or by torch, and there is no CPU
+fallback: if the shared library has not been built the import of the library
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+
+MOE_F32, MOE_BF16 = 0, 1
+STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTYPE", -4: "MOE_ERR_WORKSPACE",
+          -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE"}
+
+EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
+           "moe_predict_next", "moe_expert_ffn", "moe_layer")
+
+
+class MoeShape(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int32), ("ffn", ctypes.c_int32), ("n_experts", ctypes.c_int32),
+                ("top_k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS.get(status, status)} ({lib().moe_status_string(status).decode()})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2501_10375_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        sp = ctypes.POINTER(MoeShape)
+        L.moe_status_string.argtypes = [ctypes.c_int]
+        L.moe_status_string.restype = ctypes.c_char_p
+        for name in ("moe_workspace_bytes", "moe_route_workspace_bytes"):
+            getattr(L, name).argtypes = [sp, i32, ctypes.POINTER(sz)]
+            getattr(L, name).restype = ctypes.c_int
+        L.moe_route.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.moe_route.restype = ctypes.c_int
+        L.moe_predict_next.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_predict_next.restype = ctypes.c_int
+        L.moe_expert_ffn.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_expert_ffn.restype = ctypes.c_int
+        L.moe_layer.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.moe_layer.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MOE_F32
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise TypeError(f"unsupported storage dtype {t.dtype}")
+
+
+def make_shape(hidden: int, ffn: int, n_experts: int, top_k: int, dtype: torch.dtype) -> MoeShape:
+    code = MOE_F32 if dtype == torch.float32 else MOE_BF16 if dtype == torch.bfloat16 else -1
+    return MoeShape(hidden, ffn, n_experts, top_k, code, 0)
+
+
+def _p(t, dtype=None, shape=None, name="tensor"):
+    """Device pointer of a contiguous CUDA tensor (None -> NULL), with dtype/shape checks."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MoeError(status, where)
+
+
+def moe_workspace_bytes(shape: MoeShape, max_tokens: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().moe_workspace_bytes(ctypes.byref(shape), max_tokens, ctypes.byref(out)), "moe_workspace_bytes")
+    return out.value
+
+
+def moe_route_workspace_bytes(shape: MoeShape, max_tokens: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().moe_route_workspace_bytes(ctypes.byref(shape), max_tokens, ctypes.byref(out)),
+           "moe_route_workspace_bytes")
+    return out.value
+
+
+def alloc_workspace(shape: MoeShape, max_tokens: int, device="cuda", route_only: bool = False) -> torch.Tensor:
+    n = moe_route_workspace_bytes(shape, max_tokens) if route_only else moe_workspace_bytes(shape, max_tokens)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def moe_route(shape: MoeShape, x, w_gate, gate_bias, topk_idx, topk_w, counts, accumulate: bool, workspace):
+    T, E, k, H = x.shape[0], shape.n_experts, shape.top_k, shape.hidden
+    dt = x.dtype
+    _check(lib().moe_route(ctypes.byref(shape), T, _p(x, None, (T, H), "x"), _p(w_gate, dt, (E, H), "w_gate"),
+                           _p(gate_bias, torch.float32, (E,), "gate_bias"),
+                           _p(topk_idx, torch.int32, (T, k), "topk_idx"), _p(topk_w, torch.float32, (T, k), "topk_w"),
+                           _p(counts, torch.int32, (E,), "counts"), int(bool(accumulate)),
+                           _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()), "moe_route")
+
+
+def moe_predict_next(shape: MoeShape, x, w_gate_next, gate_bias_next, pred_idx, pred_w, pred_counts, workspace):
+    T, E, k, H = x.shape[0], shape.n_experts, shape.top_k, shape.hidden
+    dt = x.dtype
+    _check(lib().moe_predict_next(ctypes.byref(shape), T, _p(x, None, (T, H), "x"),
+                                  _p(w_gate_next, dt, (E, H), "w_gate_next"),
+                                  _p(gate_bias_next, torch.float32, (E,), "gate_bias_next"),
+                                  _p(pred_idx, torch.int32, (T, k), "pred_idx"),
+                                  _p(pred_w, torch.float32, (T, k), "pred_w"),
+                                  _p(pred_counts, torch.int32, (E,), "pred_counts"),
+                                  _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()),
+           "moe_predict_next")
+
+
+def moe_expert_ffn(shape: MoeShape, x, topk_idx, topk_w, w1, w3, w2, y, workspace):
+    T, E, k, H, F = x.shape[0], shape.n_experts, shape.top_k, shape.hidden, shape.ffn
+    dt = x.dtype
+    _check(lib().moe_expert_ffn(ctypes.byref(shape), T, _p(x, None, (T, H), "x"),
+                                _p(topk_idx, torch.int32, (T, k), "topk_idx"),
+                                _p(topk_w, torch.float32, (T, k), "topk_w"), _p(w1, dt, (E, F, H), "w1"),
+                                _p(w3, dt, (E, F, H), "w3"), _p(w2, dt, (E, H, F), "w2"), _p(y, dt, (T, H), "y"),
+                                _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()),
+           "moe_expert_ffn")
+
+
+def moe_layer(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx, topk_w,
+              counts, accumulate: bool, pred_idx, workspace):
+    T, E, k, H, F = x.shape[0], shape.n_experts, shape.top_k, shape.hidden, shape.ffn
+    dt = x.dtype
+    _check(lib().moe_layer(ctypes.byref(shape), T, _p(x, None, (T, H), "x"), _p(w_gate, dt, (E, H), "w_gate"),
+                           _p(gate_bias, torch.float32, (E,), "gate_bias"),
+                           _p(w_gate_next, dt, (E, H), "w_gate_next"),
+                           _p(gate_bias_next, torch.float32, (E,), "gate_bias_next"), _p(w1, dt, (E, F, H), "w1"),
+                           _p(w3, dt, (E, F, H), "w3"), _p(w2, dt, (E, H, F), "w2"), _p(y, dt, (T, H), "y"),
+                           _p(topk_idx, torch.int32, (T, k), "topk_idx"), _p(topk_w, torch.float32, (T, k), "topk_w"),
+                           _p(counts, torch.int32, (E,), "counts"), int(bool(accumulate)),
+                           _p(pred_idx, torch.int32, (T, k), "pred_idx"),
+                           _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()), "moe_layer")
+
+
+class LayerOutputs:
+    """Output buffers of one moe_layer call, allocated once and reused."""
+
+    def __init__(self, shape: MoeShape, max_tokens: int, dtype: torch.dtype, device="cuda", predict: bool = True):
+        k, E, H = shape.top_k, shape.n_experts, shape.hidden
+        self.y = torch.empty((max_tokens, H), dtype=dtype, device=device)
+        self.topk_idx = torch.empty((max_tokens, k), dtype=torch.int32, device=device)
+        self.topk_w = torch.empty((max_tokens, k), dtype=torch.float32, device=device)
+        self.counts = torch.zeros((E,), dtype=torch.int32, device=device)
+        self.pred_idx = torch.empty((max_tokens, k), dtype=torch.int32, device=device) if predict else None
+        self.workspace = alloc_workspace(shape, max_tokens, device)
+
+
+def run_layer(shape: MoeShape, d: dict, out: LayerOutputs, accumulate: bool = False, predict: bool = True):
+    """moe_layer on a dict of tensors as made by synth.moe_layer_inputs; returns views sized to the call."""
+    T = d["x"].shape[0]
+    pred = out.pred_idx[:T] if (predict and d.get("wg_next") is not None) else None
+    moe_layer(shape, d["x"], d["wg"], d.get("bias"), d.get("wg_next") if pred is not None else None,
+              d.get("bias_next") if pred is not None else None, d["w1"], d["w3"], d["w2"], out.y[:T],
+              out.topk_idx[:T], out.topk_w[:T], out.counts, accumulate, pred, out.workspace)
+    return {"y": out.y[:T], "idx": out.topk_idx[:T], "w": out.topk_w[:T], "counts": out.counts, "pred_idx": pred}

@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moe.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2501_10375_amd import build, moe
+
+    if not os.path.exists(moe.LIB_PATH):
+        build.build()
+    return moe.lib()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_entry_points():
+    names = _declared_functions()
+    for required in ("moe_route", "moe_expert_ffn", "moe_predict_next", "moe_layer", "moe_workspace_bytes"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(L):
+    from paper_2501_10375_amd import moe
+
+    for name in _declared_functions():
+        assert hasattr(L, name), name
+    assert set(moe.EXPORTS) == set(_declared_functions())
+
+
+def test_status_strings(L):
+    for code in range(0, -7, -1):
+        s = L.moe_status_string(code)
+        assert s and b"unknown" not in s
+    assert b"unknown" in L.moe_status_string(-99)
+
+
+def _shape(**kw):
+    from paper_2501_10375_amd import moe
+
+    base = dict(hidden=256, ffn=512, n_experts=8, top_k=2, dtype=moe.MOE_BF16, reserved=0)
+    base.update(kw)
+    return moe.MoeShape(**base)
+
+
+def test_workspace_sizes(L):
+    n = ctypes.c_size_t(0)
+    s = _shape()
+    assert L.moe_workspace_bytes(ctypes.byref(s), 64, ctypes.byref(n)) == 0
+    full = n.value
+    assert L.moe_route_workspace_bytes(ctypes.byref(s), 64, ctypes.byref(n)) == 0
+    assert 0 < n.value < full
+    # must at least hold act [A,F] bf16 and out [A,H] fp32
+    assert full >= 64 * 2 * 512 * 2 + 64 * 2 * 256 * 4
+    big = _shape(hidden=4096, ffn=14336)
+    assert L.moe_workspace_bytes(ctypes.byref(big), 4096, ctypes.byref(n)) == 0
+    assert n.value >= 8192 * 14336 * 2 + 8192 * 4096 * 4
+    assert L.moe_workspace_bytes(ctypes.byref(s), 64, None) == -1
+    assert L.moe_workspace_bytes(None, 64, ctypes.byref(n)) == -1
+    assert L.moe_workspace_bytes(ctypes.byref(s), -1, ctypes.byref(n)) == -2
+    assert L.moe_workspace_bytes(ctypes.byref(s), (1 << 20) + 1, ctypes.byref(n)) == -2
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(hidden=100), -2), (dict(ffn=0), -2), (dict(ffn=96), -2), (dict(n_experts=65), -2), (dict(n_experts=0), -2),
+    (dict(top_k=0), -2), (dict(top_k=9, n_experts=16), -2), (dict(top_k=3, n_experts=2), -2), (dict(dtype=7), -3),
+    (dict(reserved=1), -2),
+])
+def test_bad_shapes_are_rejected(L, kw, code):
+    n = ctypes.c_size_t(0)
+    s = _shape(**kw)
+    assert L.moe_workspace_bytes(ctypes.byref(s), 16, ctypes.byref(n)) == code
+    fake = ctypes.c_void_p(0x1000)
+    assert L.moe_route(ctypes.byref(s), 4, fake, fake, None, fake, fake, fake, 0, fake, 1 << 30, None) == code
+
+
+def test_entry_points_validate_before_any_device_work(L):
+    # Fake, never dereferenced addresses: every call below must fail in host-side validation.
+    s = _shape()
+    ok = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10008)
+    big = 1 << 40
+    sp = ctypes.byref(s)
+    assert L.moe_route(sp, 4, None, ok, None, ok, ok, ok, 0, ok, big, None) == -1
+    assert L.moe_route(sp, 4, ok, ok, None, ok, ok, None, 0, ok, big, None) == -1
+    assert L.moe_route(sp, 4, ok, ok, None, ok, ok, ok, 0, None, big, None) == -1
+    assert L.moe_route(sp, 4, odd, ok, None, ok, ok, ok, 0, ok, big, None) == -5
+    assert L.moe_route(sp, 4, ok, ok, odd, ok, ok, ok, 0, ok, big, None) == -5
+    assert L.moe_route(sp, -1, ok, ok, None, ok, ok, ok, 0, ok, big, None) == -2
+    assert L.moe_route(sp, 4, ok, ok, None, ok, ok, ok, 0, ok, 8, None) == -4
+    assert L.moe_predict_next(sp, 4, ok, None, None, ok, None, None, ok, big, None) == -1
+    assert L.moe_predict_next(sp, 4, ok, ok, None, None, None, None, ok, big, None) == -1
+    assert L.moe_predict_next(sp, 4, ok, ok, None, ok, odd, None, ok, big, None) == -5
+    assert L.moe_predict_next(sp, 4, ok, ok, None, ok, None, None, ok, 0, None) == -4
+    assert L.moe_expert_ffn(sp, 4, ok, ok, ok, ok, None, ok, ok, ok, big, None) == -1
+    assert L.moe_expert_ffn(sp, 4, ok, ok, ok, ok, ok, ok, odd, ok, big, None) == -5
+    n = ctypes.c_size_t(0)
+    L.moe_route_workspace_bytes(sp, 4, ctypes.byref(n))
+    assert L.moe_expert_ffn(sp, 4, ok, ok, ok, ok, ok, ok, ok, ok, n.value, None) == -4  # route-only size is not enough
+    args = [ok] * 14
+    assert L.moe_layer(sp, 4, ok, ok, None, ok, None, ok, ok, ok, ok, ok, ok, ok, 0, None, ok, big, None) == -1
+    assert L.moe_layer(sp, 4, ok, ok, None, None, None, ok, ok, None, ok, ok, ok, ok, 0, None, ok, big, None) == -1
+    assert L.moe_layer(sp, 4, ok, ok, None, None, None, ok, ok, ok, ok, ok, ok, ok, 0, None, ok, 16, None) == -4
+    assert L.moe_layer(None, 4, ok, ok, None, None, None, ok, ok, ok, ok, ok, ok, ok, 0, None, ok, big, None) == -1
+    # zero tokens with nothing to clear is accepted without touching the device
+    assert L.moe_expert_ffn(sp, 0, ok, ok, ok, ok, ok, ok, ok, ok, big, None) == 0
+    assert L.moe_predict_next(sp, 0, ok, ok, None, ok, None, None, ok, big, None) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    from paper_2501_10375_amd import moe
+
+    s = moe.make_shape(256, 512, 8, 2, torch.bfloat16)
+    x = torch.zeros((4, 256), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        moe.moe_route(s, x, x, None, x, x, x, False, x)

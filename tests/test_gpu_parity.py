@@ -1,0 +1,169 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, element by element,
+at sizes the oracle finishes in seconds: several tiles, ragged tails, degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_10375_amd import moe, synth
+from parity_util import check_layer, check_routing, host, output_error, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _run(T, H, F, E, k, dtype, seed=0, zipf=1.2, predict=True):
+    d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, seed=seed, zipf_s=zipf, with_next=predict)
+    shape = moe.make_shape(H, F, E, k, dtype)
+    out = moe.LayerOutputs(shape, max(T, 1), dtype, DEV, predict=predict)
+    res = moe.run_layer(shape, d, out, predict=predict)
+    return d, shape, out, res
+
+
+def test_config0_tiny_fp32_layer(oracle):
+    d, shape, out, res = _run(64, 256, 512, 8, 2, torch.float32)
+    r = check_layer(oracle, d, shape, res, torch.float32, label="config0")
+    print("config0", r)
+    assert r["compared_tokens"] >= 60
+
+
+@pytest.mark.parametrize("T,H,F,E,k", [
+    (300, 256, 512, 8, 2),     # several 128-slot tiles per expert, ragged tails
+    (129, 128, 192, 4, 2),     # F not a multiple of the 128 feature tile
+    (77, 64, 64, 16, 2),       # smallest legal widths, many cold experts
+    (200, 256, 256, 8, 1),     # top-1
+    (50, 128, 256, 8, 4),      # top-4
+    (40, 128, 128, 64, 8),     # widest router, top-8
+    (17, 256, 512, 8, 2),      # just above the decode threshold
+])
+def test_bf16_prefill_path(oracle, T, H, F, E, k):
+    d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
+    r = check_layer(oracle, d, shape, res, torch.bfloat16, label=f"bf16 T={T}")
+    print(r)
+
+
+@pytest.mark.parametrize("T,H,F,E,k", [
+    (1, 256, 512, 8, 2), (5, 256, 512, 8, 2), (16, 256, 512, 8, 2), (8, 512, 1600, 16, 2), (3, 64, 64, 4, 1),
+    (16, 128, 320, 8, 8), (7, 2048, 1024, 8, 2),
+])
+def test_bf16_decode_path(oracle, T, H, F, E, k):
+    d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
+    r = check_layer(oracle, d, shape, res, torch.bfloat16, label=f"decode T={T}")
+    print(r)
+
+
+@pytest.mark.parametrize("T,H,F,E,k", [(100, 128, 192, 8, 2), (5, 64, 128, 4, 2), (130, 256, 64, 16, 3)])
+def test_fp32_path(oracle, T, H, F, E, k):
+    d, shape, out, res = _run(T, H, F, E, k, torch.float32)
+    r = check_layer(oracle, d, shape, res, torch.float32, label=f"fp32 T={T}")
+    print(r)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T", [9, 150])
+def test_layer_equals_route_predict_ffn_bitwise(dtype, T):
+    H, F, E, k = 256, 512, 8, 2
+    d, shape, out, res = _run(T, H, F, E, k, dtype)
+    idx = torch.empty((T, k), dtype=torch.int32, device=DEV)
+    w = torch.empty((T, k), dtype=torch.float32, device=DEV)
+    counts = torch.full((E,), -7, dtype=torch.int32, device=DEV)
+    pidx = torch.empty((T, k), dtype=torch.int32, device=DEV)
+    pw = torch.empty((T, k), dtype=torch.float32, device=DEV)
+    pcounts = torch.full((E,), -7, dtype=torch.int32, device=DEV)
+    y = torch.empty((T, H), dtype=dtype, device=DEV)
+    ws = moe.alloc_workspace(shape, T)
+    moe.moe_route(shape, d["x"], d["wg"], d["bias"], idx, w, counts, False, ws)
+    moe.moe_predict_next(shape, d["x"], d["wg_next"], d["bias_next"], pidx, pw, pcounts, ws)
+    moe.moe_expert_ffn(shape, d["x"], idx, w, d["w1"], d["w3"], d["w2"], y, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, res["idx"]) and torch.equal(w, res["w"]) and torch.equal(counts, res["counts"])
+    assert torch.equal(pidx, res["pred_idx"])
+    assert torch.equal(y.view(torch.uint8), res["y"].view(torch.uint8))
+    assert pcounts.sum().item() == T * k
+    assert torch.equal(pcounts, torch.bincount(pidx.flatten().long(), minlength=E).int())
+    assert torch.all((pw.sum(1) - 1).abs() < 1e-5)
+
+
+@pytest.mark.parametrize("T", [8, 260])
+def test_repeatable_and_independent_of_workspace_contents(T):
+    H, F, E, k, dtype = 256, 512, 8, 2, torch.bfloat16
+    d, shape, out, res = _run(T, H, F, E, k, dtype)
+    y0, i0, c0 = res["y"].clone(), res["idx"].clone(), res["counts"].clone()
+    for fill in (0xFF, 0x7F, 0x00):
+        out.workspace.fill_(fill)   # 0xFF.. is NaN in bf16 and fp32 and -1 as an index
+        out.y.fill_(0)
+        res = moe.run_layer(shape, d, out)
+        torch.cuda.synchronize()
+        assert torch.equal(res["y"].view(torch.int16), y0.view(torch.int16))
+        assert torch.equal(res["idx"], i0) and torch.equal(res["counts"], c0)
+
+
+def test_counts_accumulate_over_calls_and_zero_tokens(oracle):
+    H, F, E, k, dtype = 256, 512, 8, 2, torch.bfloat16
+    d, shape, out, res = _run(40, H, F, E, k, dtype)
+    c1 = res["counts"].clone()
+    moe.run_layer(shape, d, out, accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out.counts, 2 * c1)
+    # decode-size call adds its own tokens
+    d1 = dict(d)
+    d1["x"] = d["x"][:3].contiguous()
+    moe.run_layer(shape, d1, out, accumulate=True)
+    torch.cuda.synchronize()
+    assert out.counts.sum().item() == (40 * 2 + 3) * k
+    # zero tokens: counts untouched with accumulate, cleared without
+    d0 = dict(d)
+    d0["x"] = d["x"][:0]
+    before = out.counts.clone()
+    moe.run_layer(shape, d0, out, accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out.counts, before)
+    moe.run_layer(shape, d0, out, accumulate=False)
+    torch.cuda.synchronize()
+    assert out.counts.sum().item() == 0
+    ws = moe.alloc_workspace(shape, 1, route_only=True)
+    cnt = torch.full((E,), 5, dtype=torch.int32, device=DEV)
+    moe.moe_route(shape, d0["x"], d["wg"], None, out.topk_idx[:0], out.topk_w[:0], cnt, False, ws)
+    torch.cuda.synchronize()
+    assert cnt.sum().item() == 0
+
+
+def test_all_tokens_to_one_expert_equals_its_dense_ffn(oracle):
+    # the degenerate grouping: one expert owns every slot (k = 1, +50 bias), both paths
+    H, F, E, dtype = 256, 512, 8, torch.bfloat16
+    for T in (12, 300):
+        d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, zipf_s=None, with_next=False)
+        d["bias"] = torch.zeros(E, dtype=torch.float32, device=DEV)
+        d["bias"][5] = 50.0
+        shape = moe.make_shape(H, F, E, 1, dtype)
+        out = moe.LayerOutputs(shape, T, dtype, DEV, predict=False)
+        res = moe.run_layer(shape, d, out, predict=False)
+        torch.cuda.synchronize()
+        assert torch.all(res["idx"] == 5) and res["counts"][5].item() == T
+        assert torch.all(res["w"] == 1.0)
+        x64 = to_f64(d["x"])
+        w1, w3, w2 = to_f64(d["w1"][5]), to_f64(d["w3"][5]), to_f64(d["w2"][5])
+        g = x64 @ w1.T
+        dense = ((g / (1 + np.exp(-g))) * (x64 @ w3.T)) @ w2.T
+        assert output_error(to_f64(res["y"]), dense) <= 2e-2
+
+
+def test_routing_entry_points_alone(oracle):
+    T, H, E, k = 1000, 512, 16, 2
+    for dtype in (torch.float32, torch.bfloat16):
+        d = synth.moe_layer_inputs(T, H, 64, E, dtype, DEV, zipf_s=1.5)
+        shape = moe.make_shape(H, 64, E, k, dtype)
+        ws = moe.alloc_workspace(shape, T, route_only=True)
+        idx = torch.empty((T, k), dtype=torch.int32, device=DEV)
+        w = torch.empty((T, k), dtype=torch.float32, device=DEV)
+        counts = torch.zeros((E,), dtype=torch.int32, device=DEV)
+        moe.moe_route(shape, d["x"], d["wg"], d["bias"], idx, w, counts, False, ws)
+        torch.cuda.synchronize()
+        h = host(d)
+        ref = oracle.route(h["x"], h["wg"], h["bias"], k)
+        n_excl, _ = check_routing(idx, w, counts, ref, E, "moe_route")
+        assert n_excl < 0.02 * T
+        # same gate as "next" gate: the prediction equals the routing
+        pidx = torch.empty((T, k), dtype=torch.int32, device=DEV)
+        moe.moe_predict_next(shape, d["x"], d["wg"], d["bias"], pidx, None, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(pidx, idx)
