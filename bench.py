@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE layer on one MI355X.
+
+A "step" is one moe_layer call (routing, counts, next-layer prediction, permute, grouped SwiGLU
+experts, combine) on one batch of synthetic input that is already resident in HBM.  The headline
+workload is the Mixtral-8x7B-shaped layer (Table III of the DAOP paper: hidden 4096, 8 experts of
+FFN width 14336, top-2) at a 4096-token prefill; the same run also times single-token decode and
+the CPU oracle on the host cores.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+WORKLOADS = {
+    # name: (H, F, E, k, zipf_s, prefill_T, decode_T)
+    "mixtral": dict(H=4096, F=14336, E=8, k=2, zipf=1.2),
+    "phi": dict(H=4096, F=6400, E=16, k=2, zipf=1.5),
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--model", default="mixtral", choices=sorted(WORKLOADS))
+    ap.add_argument("--tokens", type=int, default=4096, help="tokens of the headline (prefill) workload")
+    ap.add_argument("--decode-tokens", type=int, nargs="*", default=[1], help="decode batch sizes also timed")
+    ap.add_argument("--decode-layers", type=int, default=4,
+                    help="distinct weight sets the decode loop rotates over (keeps the weights cold in cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle is timed on (0 = pick for ~15 s)")
+    return ap.parse_args()
+
+
+def time_steps(fn, steps, warmup):
+    import torch
+
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def stage_times(fn, steps):
+    """Mean per-launch GPU time of each stage (HIP events on the launch stream), over `steps` calls."""
+    import torch
+    from paper_2501_10375_amd import moe
+
+    torch.cuda.synchronize()
+    moe.moe_stage_timing_begin(steps)
+    for _ in range(steps):
+        fn()
+    return moe.moe_stage_timing_end()
+
+
+def read_traffic(key):
+    """Per-launch HBM bytes of a kernel from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(key)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures ONE MI355X: this build has no multi-GPU path (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2501_10375_amd import moe, synth
+
+    moe.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = WORKLOADS[args.model]
+    H, F, E, k = cfg["H"], cfg["F"], cfg["E"], cfg["k"]
+    dtype = torch.bfloat16
+    T = args.tokens
+    shape = moe.make_shape(H, F, E, k, dtype)
+
+    # ---- headline: prefill of one sequence, with counts and next-layer prediction ----------------
+    d = synth.moe_layer_inputs(T, H, F, E, dtype, dev, seed=0, zipf_s=cfg["zipf"], with_next=True)
+    out = moe.LayerOutputs(shape, T, dtype, dev, predict=True)
+
+    def step():
+        moe.run_layer(shape, d, out)
+
+    sec = time_steps(step, args.steps, args.warmup)
+    st = stage_times(step, args.steps)
+    counts = out.counts.cpu().tolist()
+    A = T * k
+    flops_layer = T * (12.0 * H * F + 2 * 2.0 * H * E)
+    flops_gemm1 = 4.0 * A * H * F
+    g1_ms = st["gemm1"][0]
+    roofline = {
+        "bound": "mfma", "kernel": "grouped_gemm_bf16<gemm1+swiglu>",
+        "achieved": flops_gemm1 / (g1_ms * 1e-3) / 1e12 if g1_ms > 0 else None,
+        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": (flops_gemm1 / (g1_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if g1_ms > 0 else None,
+        "traffic": read_traffic(f"{args.model}_prefill_T{T}_gemm1"),
+        "kernel_ms": g1_ms, "algorithmic_flops_per_launch": flops_gemm1,
+    }
+    result = {
+        "metric": "moe_layer_tokens_per_s", "value": T / sec, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.model}_layer_prefill_T{T}_bf16_top{k}_with_counts_and_prediction",
+                   "hidden": H, "ffn": F, "n_experts": E, "top_k": k, "tokens": T, "gate_bias": f"zipf({cfg['zipf']})",
+                   "counts": counts},
+        "layer_tflops": flops_layer / sec / 1e12, "layer_frac_of_mfma_peak": flops_layer / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "stage_ms": {name: round(v[0], 5) for name, v in st.items() if v[1] > 0},
+        "roofline": roofline,
+    }
+
+    # ---- decode: a few tokens per call, weights cold (rotate over distinct weight sets) -----------
+    decode = []
+    if args.decode_tokens:
+        layers = [d] + [synth.moe_layer_inputs(1, H, F, E, dtype, dev, seed=s, zipf_s=cfg["zipf"], with_next=False)
+                        for s in range(1, max(1, args.decode_layers))]
+        for Td in args.decode_tokens:
+            xs = synth.normal((Td, H), 1000, synth.TID_X, 1.0, dtype, dev)
+            outs = moe.LayerOutputs(shape, Td, dtype, dev, predict=False)
+            calls = [dict(L, x=xs, wg_next=None, bias_next=None) for L in layers]
+            state = {"i": 0}
+
+            def dstep():
+                moe.run_layer(shape, calls[state["i"] % len(calls)], outs, predict=False)
+                state["i"] += 1
+
+            n = max(args.steps, 4 * len(calls))
+            dsec = time_steps(dstep, n, max(args.warmup, len(calls)))
+            state["i"] = 0
+            dst = stage_times(dstep, n)
+            # distinct experts hit, per weight set (the routing differs per set)
+            distinct = []
+            for c in calls:
+                moe.run_layer(shape, c, outs, predict=False)
+                distinct.append(int((outs.counts > 0).sum().item()))
+            Dm = sum(distinct) / len(distinct)
+            bytes_layer = Dm * 3.0 * H * F * 2 + 2 * Td * H * 2 + E * H * 2
+            bytes_gemm1 = Dm * 2.0 * H * F * 2
+            g1 = dst["gemm1"][0]
+            decode.append({
+                "workload": f"{args.model}_layer_decode_T{Td}_bf16", "tokens": Td, "value": Td / dsec,
+                "unit": "tokens/s", "ms_per_step": dsec * 1e3, "steps": n, "weight_sets": len(calls),
+                "distinct_experts_mean": Dm, "layer_GBps": bytes_layer / dsec / 1e9,
+                "layer_frac_of_hbm_peak": bytes_layer / dsec / 1e9 / PEAK_HBM_GBS,
+                "stage_ms": {name: round(v[0], 5) for name, v in dst.items() if v[1] > 0},
+                "roofline": {"bound": "hbm", "kernel": "dec_gemm1", "achieved": bytes_gemm1 / (g1 * 1e-3) / 1e9 if g1 > 0 else None,
+                             "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": bytes_gemm1 / (g1 * 1e-3) / 1e9 / PEAK_HBM_GBS if g1 > 0 else None,
+                             "traffic": read_traffic(f"{args.model}_decode_T{Td}_gemm1"), "kernel_ms": g1,
+                             "algorithmic_bytes_per_launch": bytes_gemm1},
+            })
+        del layers
+    result["decode"] = decode
+
+    # ---- the CPU oracle on this machine's host cores, on a bounded sample of the headline workload ----
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle
+
+        h = {key: synth.to_numpy(v) for key, v in d.items()}
+        threads = moe_oracle.num_threads()
+        t0 = time.perf_counter()
+        ref = moe_oracle.route(h["x"], h["wg"], h["bias"], k)
+        moe_oracle.predict_next(h["x"], h["wg_next"], h["bias_next"], k)
+        t_route = time.perf_counter() - t0  # all T tokens, both gates
+        n = args.cpu_sample
+        if n <= 0:
+            probe = list(range(0, T, max(1, T // threads)))[:threads]
+            t0 = time.perf_counter()
+            moe_oracle.expert_ffn(h["x"], ref["idx"], ref["w"], h["w1"], h["w3"], h["w2"], tokens=probe)
+            per_batch = time.perf_counter() - t0
+            n = int(max(threads, min(T, threads * round(15.0 / max(per_batch, 1e-3)))))
+        sample = [int(i * T / n) for i in range(n)]
+        t0 = time.perf_counter()
+        moe_oracle.expert_ffn(h["x"], ref["idx"], ref["w"], h["w1"], h["w3"], h["w2"], tokens=sample)
+        t_ffn = time.perf_counter() - t0
+        per_token = t_route / T + t_ffn / n
+        result["cpu_baseline"] = {
+            "value": 1.0 / per_token, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"routing + prediction on all {T} tokens ({t_route:.2f} s), expert FFN + combine on {n} evenly "
+                      f"spaced tokens ({t_ffn:.2f} s); fp64 C oracle, OpenMP over tokens",
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

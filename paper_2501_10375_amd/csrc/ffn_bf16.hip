@@ -237,6 +237,7 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
         grouped_gemm_bf16<true><<<per_xcd * kXcds, 256, 0, stream>>>(
             static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w1), static_cast<const uint16_t*>(w3), offs,
             row_of_slot, s.n_experts, s.top_k, s.ffn, s.hidden, per_xcd, act);
+        stage_mark(stream, kStageGemm1);
     }
     {
         const int tiles = max_mtiles * ((s.hidden + BF - 1) / BF);
@@ -244,8 +245,10 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
         grouped_gemm_bf16<false><<<per_xcd * kXcds, 256, 0, stream>>>(
             static_cast<const uint16_t*>(act), static_cast<const uint16_t*>(w2), nullptr, offs, row_of_slot,
             s.n_experts, s.top_k, s.hidden, s.ffn, per_xcd, out);
+        stage_mark(stream, kStageGemm2);
     }
     combine_bf16<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, static_cast<uint16_t*>(y));
+    stage_mark(stream, kStageCombine);
     return hipGetLastError();
 }
 

@@ -33,7 +33,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kMaxTok = kDecodeMaxTokens;  // 16 = columns of one MFMA
+constexpr int kMaxTok = kDecodeMaxTokens;
+static_assert(kMaxTok == 16, "an expert's tokens are the 16 columns of one 16x16x32 MFMA");
 
 struct Groups {
     int n_active;
@@ -288,9 +289,11 @@ hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* 
                                                  static_cast<const uint16_t*>(w1), static_cast<const uint16_t*>(w3),
                                                  tokens, s.top_k, s.n_experts, s.hidden, s.ffn,
                                                  static_cast<uint16_t*>(act));
+    stage_mark(stream, kStageGemm1);
     dec_gemm2<16><<<s.hidden / 16, kThreads, 0, stream>>>(static_cast<const uint16_t*>(act), topk_idx, topk_w,
                                                           static_cast<const uint16_t*>(w2), tokens, s.top_k,
                                                           s.n_experts, s.hidden, s.ffn, static_cast<uint16_t*>(y));
+    stage_mark(stream, kStageGemm2);
     return hipGetLastError();
 }
 

@@ -171,9 +171,12 @@ hipError_t launch_ffn_f32(const moe_shape_t& s, int tokens, const float* x, cons
     const int max_mtiles = (A + BM - 1) / BM + s.n_experts;
     gemm1_swiglu_f32<<<dim3(max_mtiles, s.ffn / BN), 256, 0, stream>>>(x, w1, w3, offs, row_of_slot, s.n_experts,
                                                                        s.top_k, s.hidden, s.ffn, act);
+    stage_mark(stream, kStageGemm1);
     gemm2_f32<<<dim3(max_mtiles, s.hidden / BN), 256, 0, stream>>>(act, w2, offs, s.n_experts, s.hidden, s.ffn,
                                                                   out);
+    stage_mark(stream, kStageGemm2);
     combine_f32<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, y);
+    stage_mark(stream, kStageCombine);
     return hipGetLastError();
 }
 

@@ -24,6 +24,42 @@ WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
     return L;
 }
 
+// ---- optional per-stage timing ------------------------------------------------
+namespace {
+struct StageTimer {
+    static constexpr int kMaxMarks = 8;
+    int max_calls = 0, calls = 0;
+    int cur = -1;  // index of the call being recorded
+    hipEvent_t* events = nullptr;  // [max_calls][kMaxMarks]
+    int* stage_of = nullptr;       // [max_calls][kMaxMarks], -1 = call start
+    int* n_marks = nullptr;        // [max_calls]
+};
+thread_local StageTimer* g_timer = nullptr;
+
+void stage_call_begin(hipStream_t stream) {
+    StageTimer* t = g_timer;
+    if (t == nullptr) return;
+    if (t->calls >= t->max_calls) {
+        t->cur = -1;
+        return;
+    }
+    t->cur = t->calls++;
+    t->n_marks[t->cur] = 1;
+    t->stage_of[t->cur * StageTimer::kMaxMarks] = -1;
+    (void)hipEventRecord(t->events[t->cur * StageTimer::kMaxMarks], stream);
+}
+}  // namespace
+
+void stage_mark(hipStream_t stream, int stage) {
+    StageTimer* t = g_timer;
+    if (t == nullptr || t->cur < 0) return;
+    int& n = t->n_marks[t->cur];
+    if (n >= StageTimer::kMaxMarks) return;
+    t->stage_of[t->cur * StageTimer::kMaxMarks + n] = stage;
+    (void)hipEventRecord(t->events[t->cur * StageTimer::kMaxMarks + n], stream);
+    ++n;
+}
+
 namespace {
 
 constexpr int kMaxTokens = 1 << 20;
@@ -85,17 +121,21 @@ Ws carve(void* workspace, const WorkspaceLayout& L) {
 hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* gates, int n_gates, int32_t* counts,
                      int accumulate, int32_t* counts_next, bool permute, const Ws& ws, hipStream_t stream) {
     if (!permute && tokens <= kDecodeMaxTokens) {
-        return launch_route_small(s, tokens, x, gates, n_gates, counts, accumulate, counts_next, stream);
+        hipError_t e = launch_route_small(s, tokens, x, gates, n_gates, counts, accumulate, counts_next, stream);
+        stage_mark(stream, kStageRoute);
+        return e;
     }
     gates[0].hist = ws.hist;
     if (n_gates > 1) gates[1].hist = counts_next != nullptr ? ws.hist_next : nullptr;
     hipError_t e = launch_route(s, tokens, x, gates, n_gates, stream);
+    stage_mark(stream, kStageRoute);
     if (e != hipSuccess) return e;
     e = launch_finalize(s, tokens, ws.hist, gates[0].idx, counts, accumulate, permute ? ws.offs : nullptr,
                         permute ? ws.row_of_slot : nullptr, permute ? ws.slot_of : nullptr, stream);
     if (e != hipSuccess) return e;
     if (n_gates > 1 && counts_next != nullptr)
         e = launch_finalize(s, tokens, ws.hist_next, gates[1].idx, counts_next, 0, nullptr, nullptr, nullptr, stream);
+    stage_mark(stream, kStagePermute);
     return e;
 }
 
@@ -163,6 +203,7 @@ int moe_route(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
     const Ws ws = carve(workspace, L);
     if (tokens == 0)
         return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, stream));
+    stage_call_begin(stream);
     GateArgs g[1] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}};
     return dev(run_route(*shape, tokens, x, g, 1, counts, accumulate, nullptr, false, ws, stream));
 }
@@ -186,6 +227,7 @@ int moe_predict_next(const moe_shape_t* shape, int32_t tokens, const void* x, co
         if (pred_counts == nullptr) return MOE_OK;
         return dev(launch_finalize(*shape, 0, ws.hist, nullptr, pred_counts, 0, nullptr, nullptr, nullptr, stream));
     }
+    stage_call_begin(stream);
     GateArgs g[1] = {{w_gate_next, gate_bias_next, pred_idx, pred_w, nullptr}};
     return dev(run_route(*shape, tokens, x, g, 1, pred_counts, 0, nullptr, false, ws, stream));
 }
@@ -204,10 +246,12 @@ int moe_expert_ffn(const moe_shape_t* shape, int32_t tokens, const void* x, cons
     if (tokens == 0) return MOE_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Ws ws = carve(workspace, L);
+    stage_call_begin(stream);
     if (!decode_path(*shape, tokens)) {
         hipError_t e = launch_hist_from_idx(*shape, tokens, topk_idx, ws.hist, stream);
         if (e != hipSuccess) return MOE_ERR_DEVICE;
         e = launch_finalize(*shape, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, stream);
+        stage_mark(stream, kStagePermute);
         if (e != hipSuccess) return MOE_ERR_DEVICE;
     }
     return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
@@ -232,12 +276,60 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
     const Ws ws = carve(workspace, L);
     if (tokens == 0)
         return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, stream));
+    stage_call_begin(stream);
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;
     hipError_t e = run_route(*shape, tokens, x, g, n_gates, counts, accumulate, nullptr, !decode_path(*shape, tokens), ws,
                              stream);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+}
+
+int moe_stage_timing_begin(int32_t max_calls) {
+    if (max_calls <= 0 || max_calls > 65536) return MOE_ERR_SHAPE;
+    if (g_timer != nullptr) return MOE_ERR_SHAPE;
+    StageTimer* t = new StageTimer();
+    const int n = max_calls * StageTimer::kMaxMarks;
+    t->max_calls = max_calls;
+    t->events = new hipEvent_t[n];
+    t->stage_of = new int[n];
+    t->n_marks = new int[max_calls]();
+    for (int i = 0; i < n; ++i) {
+        if (hipEventCreate(&t->events[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(t->events[j]);
+            delete[] t->events; delete[] t->stage_of; delete[] t->n_marks; delete t;
+            return MOE_ERR_DEVICE;
+        }
+    }
+    g_timer = t;
+    return MOE_OK;
+}
+
+int moe_stage_timing_end(float* stage_ms, int32_t* stage_launches) {
+    StageTimer* t = g_timer;
+    if (t == nullptr) return MOE_ERR_SHAPE;
+    g_timer = nullptr;
+    int rc = MOE_OK;
+    double sum[MOE_NUM_STAGES] = {0};
+    int cnt[MOE_NUM_STAGES] = {0};
+    for (int c = 0; c < t->calls; ++c) {
+        const int n = t->n_marks[c];
+        hipEvent_t* ev = t->events + c * StageTimer::kMaxMarks;
+        if (n > 0 && hipEventSynchronize(ev[n - 1]) != hipSuccess) rc = MOE_ERR_DEVICE;
+        for (int i = 1; i < n; ++i) {
+            float ms = 0.f;
+            const int st = t->stage_of[c * StageTimer::kMaxMarks + i];
+            if (hipEventElapsedTime(&ms, ev[i - 1], ev[i]) != hipSuccess) rc = MOE_ERR_DEVICE;
+            else if (st >= 0 && st < MOE_NUM_STAGES) { sum[st] += ms; ++cnt[st]; }
+        }
+    }
+    for (int s = 0; s < MOE_NUM_STAGES; ++s) {
+        if (stage_ms != nullptr) stage_ms[s] = cnt[s] > 0 ? (float)(sum[s] / cnt[s]) : 0.f;
+        if (stage_launches != nullptr) stage_launches[s] = cnt[s];
+    }
+    for (int i = 0; i < t->max_calls * StageTimer::kMaxMarks; ++i) (void)hipEventDestroy(t->events[i]);
+    delete[] t->events; delete[] t->stage_of; delete[] t->n_marks; delete t;
+    return rc;
 }
 
 }  // extern "C"

@@ -15,7 +15,7 @@ constexpr int kRouteTokensPerBlock = 16;
 // Calls with at most this many tokens take the decode path: one fused routing
 // kernel and two weight-streaming kernels that group tokens per expert on the
 // fly, without a permutation in the workspace.
-constexpr int kDecodeMaxTokens = 32;
+constexpr int kDecodeMaxTokens = 16;
 
 // Rows (tokens) per M-tile of the grouped GEMMs; an M-tile never spans two experts.
 constexpr int kTileTokensF32 = 64;
@@ -47,6 +47,11 @@ struct GateArgs {
     float* wts;        // [T, k] or null
     int32_t* hist;     // [n_blocks, E] or null
 };
+
+// Stage ids of the optional per-stage timing (moe_stage_timing_begin/end in moe.h).
+enum Stage { kStageRoute = 0, kStagePermute = 1, kStageGemm1 = 2, kStageGemm2 = 3, kStageCombine = 4 };
+// Records "stage `stage` ends here" on `stream`; a no-op unless timing is active on this thread.
+void stage_mark(hipStream_t stream, int stage);
 
 // ---- launchers (each returns hipGetLastError() after enqueueing) ----------
 

@@ -22,7 +22,8 @@ STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTY
           -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE"}
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
-           "moe_predict_next", "moe_expert_ffn", "moe_layer")
+           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_stage_timing_begin", "moe_stage_timing_end")
+STAGES = ("route", "permute", "gemm1", "gemm2", "combine")
 
 
 class MoeShape(ctypes.Structure):
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn.restype = ctypes.c_int
         L.moe_layer.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.moe_layer.restype = ctypes.c_int
+        L.moe_stage_timing_begin.argtypes = [i32]
+        L.moe_stage_timing_begin.restype = ctypes.c_int
+        L.moe_stage_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.moe_stage_timing_end.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -166,6 +171,18 @@ def moe_layer(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next
                            _p(counts, torch.int32, (E,), "counts"), int(bool(accumulate)),
                            _p(pred_idx, torch.int32, (T, k), "pred_idx"),
                            _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()), "moe_layer")
+
+
+def moe_stage_timing_begin(max_calls: int):
+    _check(lib().moe_stage_timing_begin(max_calls), "moe_stage_timing_begin")
+
+
+def moe_stage_timing_end() -> dict:
+    """{stage name: (mean ms per launch, launches)} for the calls since moe_stage_timing_begin."""
+    ms = (ctypes.c_float * len(STAGES))()
+    n = (ctypes.c_int32 * len(STAGES))()
+    _check(lib().moe_stage_timing_end(ms, n), "moe_stage_timing_end")
+    return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(STAGES)}
 
 
 class LayerOutputs:

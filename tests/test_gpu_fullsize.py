@@ -1,0 +1,70 @@
+"""Parity at the benchmark's full sizes (Table III shapes), in the launch configuration bench.py
+times: routing, counts and prediction on every token; layer outputs on sampled tokens the oracle
+can compute one by one; count invariants on everything."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_10375_amd import moe, synth
+from parity_util import check_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+MIXTRAL = dict(H=4096, F=14336, E=8, k=2, zipf=1.2)
+PHI = dict(H=4096, F=6400, E=16, k=2, zipf=1.5)
+
+
+@pytest.fixture(scope="module")
+def mixtral():
+    c = MIXTRAL
+    d = synth.moe_layer_inputs(4096, c["H"], c["F"], c["E"], torch.bfloat16, DEV, seed=0, zipf_s=c["zipf"])
+    yield d
+    del d
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def phi():
+    c = PHI
+    d = synth.moe_layer_inputs(2048, c["H"], c["F"], c["E"], torch.bfloat16, DEV, seed=0, zipf_s=c["zipf"])
+    yield d
+    del d
+    torch.cuda.empty_cache()
+
+
+def _layer(oracle, d, c, T, n_sample, label):
+    shape = moe.make_shape(c["H"], c["F"], c["E"], c["k"], torch.bfloat16)
+    call = dict(d, x=d["x"][:T].contiguous())
+    out = moe.LayerOutputs(shape, T, torch.bfloat16, DEV)
+    res = moe.run_layer(shape, call, out)
+    torch.cuda.synchronize()
+    assert int(res["counts"].sum().item()) == T * c["k"]
+    tokens = None if n_sample >= T else np.unique(np.linspace(0, T - 1, n_sample).astype(int))
+    r = check_layer(oracle, call, shape, res, torch.bfloat16, tokens=tokens, label=label)
+    print(label, r, "counts", res["counts"].tolist(), flush=True)
+    assert r["excluded"] <= max(2, 0.01 * T)
+    return r, res
+
+
+@pytest.mark.parametrize("T", [1, 8, 16])
+def test_mixtral_decode(oracle, mixtral, T):
+    _layer(oracle, mixtral, MIXTRAL, T, T, f"mixtral decode T={T}")
+
+
+def test_mixtral_32_tokens(oracle, mixtral):
+    _layer(oracle, mixtral, MIXTRAL, 32, 32, "mixtral T=32")
+
+
+@pytest.mark.parametrize("T", [512, 4096])
+def test_mixtral_prefill(oracle, mixtral, T):
+    r, res = _layer(oracle, mixtral, MIXTRAL, T, 24, f"mixtral prefill T={T}")
+    share = res["counts"].float() / res["counts"].sum()
+    assert share[0] > 0.3 and share[-1] < 0.06  # the Zipf(1.2) skew of the benchmark recipe
+
+
+def test_phi_prefill_and_decode(oracle, phi):
+    r, res = _layer(oracle, phi, PHI, 2048, 24, "phi prefill T=2048")
+    top4 = torch.sort(res["counts"], descending=True).values[:4].sum().item() / res["counts"].sum().item()
+    assert top4 > 0.8  # four experts take most tokens (load-imbalance stress)
+    _layer(oracle, phi, PHI, 1, 1, "phi decode T=1")

@@ -130,7 +130,7 @@ def test_counts_accumulate_over_calls_and_zero_tokens(oracle):
 def test_all_tokens_to_one_expert_equals_its_dense_ffn(oracle):
     # the degenerate grouping: one expert owns every slot (k = 1, +50 bias), both paths
     H, F, E, dtype = 256, 512, 8, torch.bfloat16
-    for T in (12, 300):
+    for T in (12, 16, 17, 32, 300):
         d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, zipf_s=None, with_next=False)
         d["bias"] = torch.zeros(E, dtype=torch.float32, device=DEV)
         d["bias"][5] = 50.0
