@@ -23,6 +23,7 @@
 //   dec_gemm1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f])   a = t*k + j, e = idx[a]
 //   dec_gemm2: y[t, h]   = sum over the token's experts (ascending expert id) of
 //                          w[a] * (act[a] . w2[e, h]),  fp32, one rounding to bf16
+#include "bf16_utils.h"
 #include "moe_internal.h"
 
 namespace moe {
@@ -42,13 +43,6 @@ struct Groups {
     int cnt[64];            // tokens of that expert (<= 16)
     int assign[64][kMaxTok];  // their assignment ids t*k + j, ascending
 };
-
-__device__ inline uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
 
 // Builds the per-expert token lists; call with all threads, ends with a barrier.
 __device__ void build_groups(Groups& g, const int32_t* __restrict__ idx, int A, int E) {
@@ -171,8 +165,7 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
                         gs += red[par][w][0][p][r];
                         us += red[par][w][1][p][r];
                     }
-                    const float v = gs / (1.f + __expf(-gs)) * us;
-                    act[(size_t)g.assign[d][c] * F + f0 + 4 * (p >> 4) + r] = f32_to_bf16_rne(v);
+                    act[(size_t)g.assign[d][c] * F + f0 + 4 * (p >> 4) + r] = to_bf16(swiglu(gs, us));
                 }
             }
             accg = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -262,20 +255,8 @@ __global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict
     __syncthreads();
     if (tid < T * 16) {
         const int t = tid >> 4, r = tid & 15;
-        y[(size_t)t * H + h0 + r] = f32_to_bf16_rne(yacc[t][r]);
+        y[(size_t)t * H + h0 + r] = to_bf16(yacc[t][r]);
     }
-}
-
-int compute_units() {
-    static int cached[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
-    }
-    return cached[dev];
 }
 
 }  // namespace

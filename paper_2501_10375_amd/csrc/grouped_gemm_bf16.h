@@ -1,0 +1,417 @@
+// Grouped bf16 GEMM for the expert FFN on the CDNA4 matrix cores (device code).
+//
+// Computes, for one (expert, 256-slot tile, feature tile) per workgroup,
+//   NMAT = 2 (gemm1): act[slot, f] = silu(tok[slot] . wa[e, f]) * (tok[slot] . wb[e, f])   (bf16 out)
+//   NMAT = 1 (gemm2): out[slot, n] = tok[slot] . wa[e, n]                                  (fp32 out)
+// where tok rows are gathered rows of x (gemm1) or rows of act (gemm2), and every
+// operand is K-contiguous ("row . row" contraction, no transposes anywhere).
+//
+// Organisation (gfx950):
+//   * Workgroup tile 256 slots x 256 weight rows (NMAT = 2: 128 features of each
+//     matrix), K in steps of BK.  WT x WW wavefronts (slot groups x weight-row
+//     groups); each owns (256/WT) x (256/WW) outputs as v_mfma_f32_32x32x16_bf16
+//     tiles.  Weights are the MFMA "A" operand, slot rows the "B" operand, so a
+//     lane ends up holding 4 consecutive output features of one slot.
+//   * Operand tiles go HBM/L2 -> LDS directly (global_load_lds_dwordx4, no
+//     register staging), STAGES tiles deep.  Each lane supplies its own global
+//     address, which is how gathered rows and the XOR swizzle are expressed: the
+//     16-byte piece that must land at LDS position p is fetched by the lane
+//     whose data lands at p.  The swizzle makes the ds_read_b128 operand reads
+//     bank-conflict free.
+//   * The loads are issued from inline asm so the compiler does not serialise
+//     them against the LDS reads of other stages; completion is enforced by hand:
+//     s_waitcnt vmcnt(n) on the issuing wavefront, then a workgroup barrier,
+//     before any wavefront reads the stage.  One barrier per K step.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "bf16_utils.h"
+
+namespace moe {
+namespace gg {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+constexpr int kBT = 256;      // slots per workgroup tile
+constexpr int kBW = 256;      // weight rows per workgroup tile (all matrices together)
+constexpr int kXcds = 8;
+
+// Tile list.  The number of real tiles depends on the routing (sum over experts of
+// ceil(count / 256) slot tiles, times the feature tiles) and is only known on the device, so
+// every workgroup derives it from `offs`.  Tile order: expert, group of kGroup slot tiles, feature
+// tile, slot tile within the group.  32 consecutive tiles (what the 32 CUs of one XCD work on at
+// one time) are then about 8 slot tiles x 4 feature tiles of one expert: 12 distinct operand tiles
+// feed 32 workgroups through the XCD's L2, which is what keeps traffic from HBM and the
+// memory-side cache near its minimum.
+constexpr int kGroup = 8;
+
+__device__ inline int count_tiles(const int32_t* __restrict__ offs, int E, int n_ftiles) {
+    int total = 0;
+    for (int i = 0; i < E; ++i) total += (offs[i + 1] - offs[i] + kBT - 1) / kBT;
+    return total * n_ftiles;
+}
+
+__device__ inline void tile_of(const int32_t* __restrict__ offs, int E, int n_ftiles, int id, int& e, int& slot0,
+                               int& rows, int& ft) {
+    int acc = 0;
+    e = 0; slot0 = 0; rows = 1; ft = 0;
+    for (int i = 0; i < E; ++i) {
+        const int c = offs[i + 1] - offs[i];
+        const int mt = (c + kBT - 1) / kBT;
+        const int tiles = mt * n_ftiles;
+        if (id < acc + tiles) {
+            const int local = id - acc;
+            const int grp = local / (kGroup * n_ftiles);  // full groups come first
+            const int in_grp = local - grp * (kGroup * n_ftiles);
+            const int gsize = min(kGroup, mt - grp * kGroup);
+            ft = in_grp / gsize;
+            const int m = grp * kGroup + (in_grp - ft * gsize);
+            e = i;
+            slot0 = offs[i] + m * kBT;
+            rows = min(kBT, c - m * kBT);
+            return;
+        }
+        acc += tiles;
+    }
+}
+
+// Timing-only rendezvous of the workgroups that share an XCD (see persistent()).  It bounds its
+// own wait, so it can never hang and never affects results: if a workgroup is late the others
+// simply go on without it.
+constexpr int kMaxRendezvousSpins = 64;
+__device__ inline void xcd_rendezvous(int32_t* counter, int target) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int spins = 0; spins < kMaxRendezvousSpins; ++spins) {
+            if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
+            __builtin_amdgcn_s_sleep(16);
+        }
+    }
+    __syncthreads();
+}
+
+// 16 bytes per lane from `gptr` to LDS byte address lds_base + lane * 16 (lds_base wave-uniform).
+__device__ inline void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+
+template <int N>
+__device__ inline void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier that orders LDS traffic only (no wait on outstanding global loads).
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// LDS swizzle: the 16-byte piece `chunk` of tile row `row` is stored at piece position
+// piece(row, chunk) of that row.  The LDS has 64 four-byte banks (256 bytes per cycle), so a
+// ds_read_b128 serves 16 lanes per cycle; the lanes of one MFMA operand read sit on 16
+// consecutive rows at the same chunk, and the XOR below spreads them over all 64 banks.
+template <int BK>
+struct Swz;
+template <>
+struct Swz<64> {  // 128-byte rows, 8 pieces; two rows span the 64 banks
+    static __device__ inline int piece(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+};
+template <>
+struct Swz<32> {  // 64-byte rows, 4 pieces; four rows span the 64 banks
+    static __device__ inline int piece(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
+};
+
+#ifdef MOE_GEMM_CLOCK_PROBE
+__device__ long long g_clock_probe[24];
+#endif
+
+template <int NMAT, int BK, int STAGES, int WT, int WW, int DBG = 0>
+struct Gemm {
+    static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int kTF = 256 / WT / 32;                  // 32-slot MFMA tiles per wavefront
+    static constexpr int kWF = 256 / WW / 32;                  // 32-row weight MFMA tiles per wavefront
+    static constexpr int kStageRows = 256 / kWaves;            // rows of each operand a wavefront stages
+    static_assert(kWF % NMAT == 0, "a wavefront needs the same features of every matrix");
+    static constexpr int kRowBytes = BK * 2;
+    static constexpr int kTileBytes = 256 * kRowBytes;         // one operand tile of one stage
+    static constexpr int kStageBytes = 2 * kTileBytes;         // slots + weights
+    static constexpr int kLdsBytes = STAGES * kStageBytes;
+    static constexpr int kRowsPerLoad = 1024 / kRowBytes;      // rows covered by one wavefront-wide 1 KB load
+    static constexpr int kLoadsPerOperand = kStageRows / kRowsPerLoad;
+    static constexpr int kLoads = 2 * kLoadsPerOperand;        // loads per thread per stage
+    static constexpr int kPieces = kRowBytes / 16;
+    static constexpr int kKSteps = BK / 16;
+    static constexpr int kBF = kBW / NMAT;                     // features per tile (per matrix)
+
+    // tok_base: gemm1 -> x [T, K] rows gathered via row_of_slot / topk; gemm2 -> act [A, K] rows = slots.
+    // wa, wb: [E, N, K]; dst: gemm1 -> bf16 [A, N]; gemm2 -> fp32 [A, N].
+    // Persistent schedule: the grid is one workgroup per CU.  Workgroup b belongs to XCD b % 8 (the
+    // hardware deals workgroups round-robin to the XCDs) and is its member b / 8.  Each XCD owns one
+    // contiguous eighth of the tile list and works through it in rounds of `wgs_per_xcd` consecutive
+    // tiles, one per member.  Before each new round the members meet (xcd_rendezvous), so they walk
+    // K in step and every operand line is pulled into the XCD's L2 once per round instead of once
+    // per workgroup.  `sync` points at 8 counters that are zero when the kernel starts.
+    static __device__ void persistent(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
+                                      const uint16_t* __restrict__ wb, const int32_t* __restrict__ offs,
+                                      const int32_t* __restrict__ row_of_slot, int E, int topk, int N, int K,
+                                      void* __restrict__ dst, int32_t* __restrict__ sync, unsigned char* lds) {
+        const int n_ftiles = (N + kBF - 1) / kBF;
+        const int total = count_tiles(offs, E, n_ftiles);
+        const int xcd = blockIdx.x % kXcds, member = blockIdx.x / kXcds, wgs_per_xcd = gridDim.x / kXcds;
+        const int chunk = (total + kXcds - 1) / kXcds;
+        const int first = xcd * chunk, last = min(total, first + chunk);
+        const int rounds = (max(last - first, 0) + wgs_per_xcd - 1) / wgs_per_xcd;
+        for (int r = 0; r < rounds; ++r) {
+            if (r > 0) xcd_rendezvous(sync + xcd, r * wgs_per_xcd);
+            const int id = first + r * wgs_per_xcd + member;
+            if (id < last) {
+                int e, slot0, rows, ft;
+                tile_of(offs, E, n_ftiles, id, e, slot0, rows, ft);
+                if (DBG & 4) { e = 0; slot0 = 0; rows = 256; ft = 0; }  // probe: every tile reads the same operands
+                tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft);
+            }
+        }
+    }
+
+    static __device__ void tile(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
+                                const uint16_t* __restrict__ wb, const int32_t* __restrict__ row_of_slot, int topk,
+                                int N, int K, void* __restrict__ dst, unsigned char* lds, int e, int slot0, int rows,
+                                int ft) {
+        const int n0 = ft * kBF;
+#ifdef MOE_GEMM_CLOCK_PROBE
+        const long long probe_c0 = __builtin_readcyclecounter(), probe_w0 = wall_clock64();
+        long long probe_w1 = 0;
+#endif
+
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
+        const int wt = wave % WT, wq = wave / WT;  // slot group, weight-row group
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
+
+        // ---- staging addresses: this wavefront stages rows [wave, wave + 1) * kStageRows of each operand
+        const int lrow = lane / kPieces;                       // row within a 1 KB load
+        const int lpiece = lane % kPieces;                     // LDS piece position within the row
+        const char* gp[kLoads];
+#pragma unroll
+        for (int q = 0; q < kLoadsPerOperand; ++q) {
+            const int r = wave * kStageRows + q * kRowsPerLoad + lrow;  // row in the 256-row operand tile
+            const int chunk = Swz<BK>::piece(r, lpiece);        // global piece that belongs at this position
+            const int slot = slot0 + min(r, rows - 1);          // rows past the end re-read the last valid row
+            const int src = (NMAT == 2) ? row_of_slot[slot] / topk : slot;
+            gp[q] = reinterpret_cast<const char*>(tok_base + (size_t)src * K) + chunk * 16;
+            // weight rows: NMAT == 2 -> rows 0..127 are wa features, 128..255 wb features
+            const int mat = (NMAT == 2) ? (r >> 7) : 0;
+            const int f = min(n0 + ((NMAT == 2) ? (r & 127) : r), N - 1);
+            const uint16_t* wsrc = (mat == 0) ? wa : wb;
+            gp[kLoadsPerOperand + q] = reinterpret_cast<const char*>(wsrc + ((size_t)e * N + f) * K) + chunk * 16;
+        }
+        const int KT = K / BK;
+        const uint32_t stage_off_tok = (uint32_t)(wave * kStageRows * kRowBytes);
+        const uint32_t stage_off_w = (uint32_t)(kTileBytes + wave * kStageRows * kRowBytes);
+
+        // The loads of one stage are issued in kKSteps parts, one per k16 step of the tile being
+        // computed, and within a step one at a time between MFMAs (see step() below).
+        static_assert(kLoads % kKSteps == 0, "loads per stage must split evenly over the k16 steps");
+        constexpr int kLoadsPerPart = kLoads / kKSteps;
+        auto dma_one = [&](int stage, int kt, int l) {
+            const uint32_t base = lds0 + (uint32_t)stage * kStageBytes;
+            dma16(gp[l] + (size_t)kt * kRowBytes,
+                  base + (l < kLoadsPerOperand ? stage_off_tok : stage_off_w) + (l % kLoadsPerOperand) * 1024);
+        };
+
+        f32x16 acc[kWF][kTF];  // [weight frag][slot frag]
+#pragma unroll
+        for (int j = 0; j < kWF; ++j)
+#pragma unroll
+            for (int i = 0; i < kTF; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+        // ---- operand read offsets (bytes within an operand tile), per k16 step
+        const int frow = lane & 31, fhalf = lane >> 5;
+        // Weight frag j: NMAT == 2 -> matrix j / (kWF/2), feature tile j % (kWF/2) of this wavefront's
+        // features [wq * kFeatPerWave, +kFeatPerWave); NMAT == 1 -> weight rows wq * 32 * kWF + 32 j.
+        constexpr int kFragsPerMat = kWF / NMAT;
+        constexpr int kFeatPerWave = 32 * kFragsPerMat;
+        int trow[kTF], wrow[kWF];
+#pragma unroll
+        for (int i = 0; i < kTF; ++i) trow[i] = wt * (32 * kTF) + i * 32 + frow;
+#pragma unroll
+        for (int j = 0; j < kWF; ++j)
+            wrow[j] = (j / kFragsPerMat) * 128 * (NMAT - 1) + wq * kFeatPerWave + (j % kFragsPerMat) * 32 + frow;
+
+        // Operand fragments are double-buffered in registers (buffer = k16 step & 1).  One pipeline
+        // step issues the MFMAs of one k16 step and, BETWEEN them one for one, the LDS reads of the
+        // next step's fragments (into the other buffer) and this wavefront's share of the global->LDS
+        // loads of a later tile.  Interleaving matters: a burst of ds_reads from all wavefronts right
+        // after a barrier fills the LDS command queue and blocks the issuing wavefronts, MFMAs
+        // included; one read per MFMA keeps the matrix pipe fed while the queue drains.  The MFMAs of a
+        // tile's LAST step run after the next tile's barrier, paired with that tile's first reads, so
+        // the matrix pipe also has work while the wavefronts re-synchronise.
+        static_assert(kKSteps % 2 == 0, "fragment buffers alternate per k16 step");
+        constexpr int kM = kWF * kTF, kR = kWF + kTF;
+        static_assert(kR + kLoadsPerPart <= kM, "a step has one slot per MFMA for its reads and loads");
+        bf16x8 tf[2][kTF], wf[2][kWF];
+        auto read_one = [&](int stage, int ks, int buf, int idx) {
+            const unsigned char* st = lds + stage * kStageBytes;
+            if (idx < kWF)
+                wf[buf][idx] = *reinterpret_cast<const bf16x8*>(
+                    st + kTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
+            else
+                tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
+                    st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
+        };
+        constexpr bool kCompute = (DBG & 3) != 2, kStream = (DBG & 3) != 1;
+        // mfma: issue the MFMAs of buffer mbuf.  read: fetch fragments (rstage, rks) into buffer rbuf.
+        // dma: issue part dpart of tile dkt's loads into stage dstage.
+        auto step = [&](auto mfma, int mbuf, auto read, int rstage, int rks, int rbuf, bool dma, int dstage, int dkt,
+                        int dpart) {
+#pragma unroll
+            for (int m = 0; m < kM; ++m) {
+                if (decltype(mfma)::value && kCompute) {
+                    const int i = m / kWF, j = m % kWF;
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
+                }
+                if (decltype(read)::value && kCompute && m < kR) read_one(rstage, rks, rbuf, m);
+                if (m >= kM - kLoadsPerPart && dma) dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        using Yes = std::true_type;
+        using No = std::false_type;
+
+        // prologue: STAGES - 1 tiles in flight
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < KT) {
+#pragma unroll
+                for (int l = 0; l < kLoads; ++l) dma_one(s, s, l);
+            }
+        for (int kt0 = 0; kt0 < KT; kt0 += STAGES) {
+#pragma unroll
+            for (int s = 0; s < STAGES; ++s) {
+                const int kt = kt0 + s;
+                if (kt < KT) {
+                    // tile kt must have landed; up to STAGES - 2 younger tiles may stay in flight
+                    if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * kLoads>();
+                    else wait_vmcnt<0>();
+                    lds_barrier();
+#ifdef MOE_GEMM_CLOCK_PROBE
+                    if (kt == 0) probe_w1 = wall_clock64();
+#endif
+                    const bool more = kt + STAGES - 1 < KT && kStream;
+                    const int ns = (s + STAGES - 1) % STAGES;
+                    // last step of tile kt - 1 (buffer 1) with the first reads of tile kt (buffer 0)
+                    if (kt > 0) step(Yes{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
+                    else step(No{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
+#pragma unroll
+                    for (int ks = 0; ks + 1 < kKSteps; ++ks)
+                        step(Yes{}, ks & 1, Yes{}, s, ks + 1, (ks + 1) & 1, more, ns, kt + STAGES - 1, ks + 1);
+                }
+            }
+        }
+        step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, 0);
+
+#ifdef MOE_GEMM_CLOCK_PROBE
+        const long long probe_c2 = __builtin_readcyclecounter(), probe_w2 = wall_clock64();
+#endif
+        // ---- epilogue: transpose through LDS so that global stores are whole contiguous rows.
+        // MFMA 32x32 result: lane holds column (slot) lane & 31 and rows (weight rows)
+        // 8 * (r / 4) + 4 * (lane / 32) + (r % 4), r = 0..15, i.e. 4 consecutive features per r / 4.
+        // LDS rows are XOR-swizzled in 16-byte units so the row-wise read-back is conflict free.
+        lds_barrier();  // every wavefront is done reading operand tiles; no load is outstanding
+        if (NMAT == 2) {
+            // [256 slots][128 features] bf16, 256-byte rows, unit v of row r at position v ^ (r & 15)
+#pragma unroll
+            for (int i = 0; i < kTF; ++i) {
+                const int row = wt * (32 * kTF) + i * 32 + frow;
+#pragma unroll
+                for (int jf = 0; jf < kFragsPerMat; ++jf) {
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int col = wq * kFeatPerWave + jf * 32 + rg * 8 + fhalf * 4;  // feature in tile
+                        float o[4];
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            o[c] = swiglu(acc[jf][i][rg * 4 + c], acc[kFragsPerMat * (NMAT - 1) + jf][i][rg * 4 + c]);
+                        uint2 pk;
+                        pk.x = pack_bf16x2(o[0], o[1]);
+                        pk.y = pack_bf16x2(o[2], o[3]);
+                        const int unit = col >> 3;
+                        *reinterpret_cast<uint2*>(lds + row * 256 + ((unit ^ (row & 15)) << 4) + (col & 4) * 2) = pk;
+                    }
+                }
+            }
+            lds_barrier();
+            for (int row = tid >> 4; row < rows; row += kThreads / 16) {
+                const int unit = tid & 15;
+                const int n = n0 + unit * 8;
+                if (n < N) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * 256 + ((unit ^ (row & 15)) << 4));
+                    *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(dst) + (size_t)(slot0 + row) * N + n) = v;
+                }
+            }
+        } else {
+            // per slot frag i: [32 * WT slots][256 features] fp32, 1 KB rows, unit v of row r at v ^ (r & 63)
+#pragma unroll
+            for (int i = 0; i < kTF; ++i) {
+                if (i > 0) lds_barrier();
+                const int lrow_e = wt * 32 + frow;
+#pragma unroll
+                for (int jf = 0; jf < kFragsPerMat; ++jf) {
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int unit = (wq * kFeatPerWave + jf * 32 + rg * 8 + fhalf * 4) >> 2;
+                        f32x4 v;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[c] = acc[jf][i][rg * 4 + c];
+                        *reinterpret_cast<f32x4*>(lds + lrow_e * 1024 + ((unit ^ (lrow_e & 63)) << 4)) = v;
+                    }
+                }
+                lds_barrier();
+                for (int lr = wave; lr < 32 * WT; lr += kWaves) {
+                    const int row = (lr >> 5) * (32 * kTF) + i * 32 + (lr & 31);  // slot in tile
+                    const int n = n0 + lane * 4;
+                    if (row < rows && n < N) {
+                        const f32x4 v = *reinterpret_cast<const f32x4*>(lds + lr * 1024 + ((lane ^ (lr & 63)) << 4));
+                        *reinterpret_cast<f32x4*>(static_cast<float*>(dst) + (size_t)(slot0 + row) * N + n) = v;
+                    }
+                }
+            }
+        }
+#ifdef MOE_GEMM_CLOCK_PROBE
+        if (blockIdx.x == 100 && threadIdx.x == 0) {
+            g_clock_probe[0] = probe_c2 - probe_c0;
+            g_clock_probe[1] = probe_w2 - probe_w0;
+            g_clock_probe[2] = probe_w1 - probe_w0;       // setup + first tile landed
+            g_clock_probe[3] = wall_clock64() - probe_w2;  // epilogue
+        }
+#endif
+    }
+};
+
+template <int NMAT, int BK, int STAGES, int WT, int WW, int DBG = 0>
+__global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uint16_t* __restrict__ tok_base,
+                                                                    const uint16_t* __restrict__ wa,
+                                                                    const uint16_t* __restrict__ wb,
+                                                                    const int32_t* __restrict__ offs,
+                                                                    const int32_t* __restrict__ row_of_slot, int E,
+                                                                    int topk, int N, int K, void* __restrict__ dst,
+                                                                    int32_t* __restrict__ sync) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
+    Gemm<NMAT, BK, STAGES, WT, WW, DBG>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, lds_dyn);
+}
+
+}  // namespace gg
+}  // namespace moe

@@ -17,6 +17,7 @@ WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
     L.offs = off;        off = align_up(off + (size_t)(s.n_experts + 1) * sizeof(int32_t));
     L.row_of_slot = off; off = align_up(off + A * sizeof(int32_t));
     L.slot_of = off;     off = align_up(off + A * sizeof(int32_t));
+    L.sync = off;        off = align_up(off + kSyncInts * sizeof(int32_t));
     L.route_end = off;
     L.act = off;         off = align_up(off + A * (size_t)s.ffn * esz);
     L.out = off;         off = align_up(off + A * (size_t)s.hidden * sizeof(float));
@@ -60,6 +61,18 @@ void stage_mark(hipStream_t stream, int stage) {
     ++n;
 }
 
+int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 namespace {
 
 constexpr int kMaxTokens = 1 << 20;
@@ -98,7 +111,7 @@ int dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
 bool decode_path(const moe_shape_t& s, int tokens) { return s.dtype == MOE_BF16 && tokens <= kDecodeMaxTokens; }
 
 struct Ws {
-    int32_t *hist, *hist_next, *offs, *row_of_slot, *slot_of;
+    int32_t *hist, *hist_next, *offs, *row_of_slot, *slot_of, *sync;
     void* act;
     float* out;
 };
@@ -111,6 +124,7 @@ Ws carve(void* workspace, const WorkspaceLayout& L) {
     w.offs = reinterpret_cast<int32_t*>(b + L.offs);
     w.row_of_slot = reinterpret_cast<int32_t*>(b + L.row_of_slot);
     w.slot_of = reinterpret_cast<int32_t*>(b + L.slot_of);
+    w.sync = reinterpret_cast<int32_t*>(b + L.sync);
     w.act = b + L.act;
     w.out = reinterpret_cast<float*>(b + L.out);
     return w;
@@ -120,9 +134,15 @@ Ws carve(void* workspace, const WorkspaceLayout& L) {
 // the workspace for the grouped GEMMs.
 hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* gates, int n_gates, int32_t* counts,
                      int accumulate, int32_t* counts_next, bool permute, const Ws& ws, hipStream_t stream) {
-    if (!permute && tokens <= kDecodeMaxTokens) {
+    if (tokens <= kDecodeMaxTokens) {
+        // Decode-size calls: one workgroup routes every token and writes the counts itself.
         hipError_t e = launch_route_small(s, tokens, x, gates, n_gates, counts, accumulate, counts_next, stream);
         stage_mark(stream, kStageRoute);
+        if (e != hipSuccess || !permute) return e;
+        e = launch_hist_from_idx(s, tokens, gates[0].idx, ws.hist, stream);
+        if (e != hipSuccess) return e;
+        e = launch_finalize(s, tokens, ws.hist, gates[0].idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, ws.sync, stream);
+        stage_mark(stream, kStagePermute);
         return e;
     }
     gates[0].hist = ws.hist;
@@ -131,10 +151,11 @@ hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* 
     stage_mark(stream, kStageRoute);
     if (e != hipSuccess) return e;
     e = launch_finalize(s, tokens, ws.hist, gates[0].idx, counts, accumulate, permute ? ws.offs : nullptr,
-                        permute ? ws.row_of_slot : nullptr, permute ? ws.slot_of : nullptr, stream);
+                        permute ? ws.row_of_slot : nullptr, permute ? ws.slot_of : nullptr,
+                        permute ? ws.sync : nullptr, stream);
     if (e != hipSuccess) return e;
     if (n_gates > 1 && counts_next != nullptr)
-        e = launch_finalize(s, tokens, ws.hist_next, gates[1].idx, counts_next, 0, nullptr, nullptr, nullptr, stream);
+        e = launch_finalize(s, tokens, ws.hist_next, gates[1].idx, counts_next, 0, nullptr, nullptr, nullptr, nullptr, stream);
     stage_mark(stream, kStagePermute);
     return e;
 }
@@ -147,7 +168,7 @@ hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_
                               static_cast<const float*>(w3), static_cast<const float*>(w2), static_cast<float*>(y),
                               ws.offs, ws.row_of_slot, ws.slot_of, static_cast<float*>(ws.act), ws.out, stream);
     return launch_ffn_bf16(s, tokens, x, w, w1, w3, w2, y, ws.offs, ws.row_of_slot, ws.slot_of, ws.act, ws.out,
-                           stream);
+                           ws.sync, stream);
 }
 
 }  // namespace
@@ -202,7 +223,7 @@ int moe_route(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Ws ws = carve(workspace, L);
     if (tokens == 0)
-        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, stream));
+        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, nullptr, stream));
     stage_call_begin(stream);
     GateArgs g[1] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}};
     return dev(run_route(*shape, tokens, x, g, 1, counts, accumulate, nullptr, false, ws, stream));
@@ -225,7 +246,7 @@ int moe_predict_next(const moe_shape_t* shape, int32_t tokens, const void* x, co
     const Ws ws = carve(workspace, L);
     if (tokens == 0) {
         if (pred_counts == nullptr) return MOE_OK;
-        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, pred_counts, 0, nullptr, nullptr, nullptr, stream));
+        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, pred_counts, 0, nullptr, nullptr, nullptr, nullptr, stream));
     }
     stage_call_begin(stream);
     GateArgs g[1] = {{w_gate_next, gate_bias_next, pred_idx, pred_w, nullptr}};
@@ -250,7 +271,7 @@ int moe_expert_ffn(const moe_shape_t* shape, int32_t tokens, const void* x, cons
     if (!decode_path(*shape, tokens)) {
         hipError_t e = launch_hist_from_idx(*shape, tokens, topk_idx, ws.hist, stream);
         if (e != hipSuccess) return MOE_ERR_DEVICE;
-        e = launch_finalize(*shape, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, stream);
+        e = launch_finalize(*shape, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, ws.sync, stream);
         stage_mark(stream, kStagePermute);
         if (e != hipSuccess) return MOE_ERR_DEVICE;
     }
@@ -275,7 +296,7 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Ws ws = carve(workspace, L);
     if (tokens == 0)
-        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, stream));
+        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, nullptr, stream));
     stage_call_begin(stream);
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;

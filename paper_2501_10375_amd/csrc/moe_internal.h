@@ -19,7 +19,7 @@ constexpr int kDecodeMaxTokens = 16;
 
 // Rows (tokens) per M-tile of the grouped GEMMs; an M-tile never spans two experts.
 constexpr int kTileTokensF32 = 64;
-constexpr int kTileTokensBf16 = 128;
+constexpr int kTileTokensBf16 = 256;
 
 struct WorkspaceLayout {
     size_t hist;         // int32 [n_blocks, E]  per-block selection histogram
@@ -27,6 +27,7 @@ struct WorkspaceLayout {
     size_t offs;         // int32 [E + 1]        exclusive scan of counts
     size_t row_of_slot;  // int32 [A]            slot -> assignment index t*k + j
     size_t slot_of;      // int32 [A]            assignment index -> slot
+    size_t sync;         // int32 [16]           rendezvous counters of the two grouped GEMMs
     size_t route_end;    // bytes needed by routing-only calls
     size_t act;          // dtype [A, F]         silu(W1 x) * (W3 x)
     size_t out;          // fp32  [A, H]         per-assignment expert output
@@ -67,9 +68,11 @@ hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t*
 // Sum block histograms into counts (counts may be null), and when
 // row_of_slot/slot_of are given build offs and the stable token->expert
 // permutation.
+// `sync` (may be null) is a block of kSyncInts counters that is cleared for the GEMMs that follow.
+constexpr int kSyncInts = 16;
 hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
                            int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
-                           int32_t* slot_of, hipStream_t stream);
+                           int32_t* slot_of, int32_t* sync, hipStream_t stream);
 
 // Decode path (tokens <= kDecodeMaxTokens): routing for up to two gates with
 // counts written directly, in one workgroup.
@@ -87,7 +90,10 @@ hipError_t launch_ffn_f32(const moe_shape_t& s, int tokens, const float* x, cons
 hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w,
                            const void* w1, const void* w3, const void* w2, void* y,
                            const int32_t* offs, const int32_t* row_of_slot, const int32_t* slot_of,
-                           void* act, float* out, hipStream_t stream);
+                           void* act, float* out, int32_t* sync, hipStream_t stream);
+
+// Number of compute units of the current device (cached per device).
+int compute_units();
 
 // Weight-streaming expert FFN, bf16 storage (tokens <= kDecodeMaxTokens).
 hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* x,

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(const int32_t* __restrict
                                                        int32_t* __restrict__ counts, int accumulate,
                                                        int32_t* __restrict__ offs,
                                                        int32_t* __restrict__ row_of_slot,
-                                                       int32_t* __restrict__ slot_of) {
+                                                       int32_t* __restrict__ slot_of, int32_t* __restrict__ sync) {
     __shared__ int total[64];
     __shared__ int before[64];
     __shared__ int base[64];
@@ -74,6 +74,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(const int32_t* __restrict
         if (blk == 0 && offs != nullptr) offs[E] = run;
     }
     if (blk == 0 && counts != nullptr && tid < E) counts[tid] = (accumulate ? counts[tid] : 0) + total[tid];
+    if (blk == 0 && sync != nullptr && tid < kSyncInts) sync[tid] = 0;
     if (row_of_slot == nullptr) return;
     const int a0 = blk * kRouteTokensPerBlock * k;
     const int n_local = min(tokens * k, a0 + kRouteTokensPerBlock * k) - a0;
@@ -100,11 +101,11 @@ hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t*
 
 hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
                            int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
-                           int32_t* slot_of, hipStream_t stream) {
+                           int32_t* slot_of, int32_t* sync, hipStream_t stream) {
     const int nb = route_blocks(tokens);
     const int grid = (row_of_slot != nullptr && nb > 0) ? nb : 1;
     finalize_kernel<<<grid, 256, 0, stream>>>(hist, nb, s.n_experts, s.top_k, tokens, idx, counts, accumulate,
-                                              offs, row_of_slot, slot_of);
+                                              offs, row_of_slot, slot_of, sync);
     return hipGetLastError();
 }
 

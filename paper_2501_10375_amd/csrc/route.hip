@@ -3,12 +3,14 @@
 // Algorithm 1; next-layer prediction of Sec. III observation 3 / Sec. IV-C,
 // which is the same computation with the next layer's gate on the same x).
 //
-// One wavefront owns one token at a time.  The 64 lanes split the hidden
-// dimension in 16-byte pieces, keep one fp32 partial sum per expert, and fold
-// the partials with a butterfly of wavefront shuffles, after which every lane
-// holds all E logits and the softmax / top-k run redundantly in registers.
-// Up to two gates (this layer's and the next layer's) are evaluated per token
-// so x comes from HBM once; the second pass over the row hits the vector cache.
+// One wavefront (or, for decode-size calls, a group of up to 16 wavefronts)
+// owns one token.  The lanes split the hidden dimension in 16-byte pieces,
+// keep one fp32 partial sum per expert, and fold the partials with a butterfly
+// of wavefront shuffles (then through LDS across the wavefronts of a group),
+// after which every lane holds all E logits and the softmax / top-k run
+// redundantly in registers.  Up to two gates (this layer's and the next
+// layer's) are evaluated per token so x comes from HBM once; the second pass
+// over the row hits the vector cache.
 #include "moe_internal.h"
 
 namespace moe {
@@ -40,17 +42,15 @@ __device__ inline void load8(const uint16_t* p, float (&v)[8]) {
     }
 }
 
-// Routes token `t` through one gate.  All lanes of the wavefront take part;
-// lane 0 writes the result and bumps the workgroup histogram in LDS.
+// Partial logits of one token against one gate over the 16-byte pieces
+// (piece index = (i * n_slices + slice) * 64 + lane) of the hidden dimension.
+// Returns with every lane holding the wavefront's sums in acc[0..E).
 template <typename scalar_t, int EPAD>
-__device__ void route_token(const scalar_t* __restrict__ xrow, const RouteParams& p, const GateArgs& g,
-                            int t, int lane, int* lds_hist) {
-    const int H = p.hidden, E = p.n_experts, k = p.top_k;
-    const scalar_t* __restrict__ wg = static_cast<const scalar_t*>(g.w);
-    float acc[EPAD];
+__device__ inline void gate_partial(const scalar_t* __restrict__ xrow, const scalar_t* __restrict__ wg, int H, int E,
+                                    int slice, int n_slices, int lane, float (&acc)[EPAD]) {
 #pragma unroll
     for (int r = 0; r < EPAD; ++r) acc[r] = 0.f;
-    for (int h = lane * 8; h < H; h += 64 * 8) {
+    for (int h = (slice * 64 + lane) * 8; h < H; h += n_slices * 64 * 8) {
         float xv[8];
         load8(xrow + h, xv);
 #pragma unroll
@@ -67,8 +67,17 @@ __device__ void route_token(const scalar_t* __restrict__ xrow, const RouteParams
     for (int r = 0; r < EPAD; ++r) {
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) acc[r] += __shfl_xor(acc[r], off, 64);
-        if (g.bias != nullptr && r < E) acc[r] += g.bias[r];
     }
+}
+
+// Softmax over the E logits in acc, k passes of arg-max, renormalised weights.
+// Every lane computes the same values; lane 0 writes them and bumps the LDS histogram.
+template <int EPAD>
+__device__ inline void select_topk(float (&acc)[EPAD], const GateArgs& g, int E, int k, int t, int lane,
+                                   int* lds_hist) {
+#pragma unroll
+    for (int r = 0; r < EPAD; ++r)
+        if (g.bias != nullptr && r < E) acc[r] += g.bias[r];
     float zmax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < EPAD; ++r)
@@ -82,7 +91,7 @@ __device__ void route_token(const scalar_t* __restrict__ xrow, const RouteParams
 #pragma unroll
     for (int r = 0; r < EPAD; ++r) acc[r] = acc[r] / denom;
 
-    // k passes of arg-max; strict '>' while scanning upward keeps the lower index on ties.
+    // strict '>' while scanning upward keeps the lower index on ties
     uint64_t taken = 0;
     int sel[8];
     float selp[8];
@@ -123,62 +132,86 @@ __device__ void route_token(const scalar_t* __restrict__ xrow, const RouteParams
     }
 }
 
-template <typename scalar_t, int EPAD>
-__global__ __launch_bounds__(256) void route_kernel(RouteParams p) {
+// 16 wavefronts per workgroup.  WPT wavefronts share one token (each takes an
+// interleaved slice of the hidden dimension; partial logits are summed through
+// LDS in slice order), so a workgroup covers 16 / WPT tokens.
+//   SMALL = false: WPT = 1, grid = ceil(T / 16); per-workgroup histograms go to gate.hist.
+//   SMALL = true : one workgroup holds the whole call (T <= 16 / WPT); counts are written directly.
+template <typename scalar_t, int EPAD, int WPT, bool SMALL>
+__global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
     __shared__ int hist[2][64];
+    __shared__ float part[(WPT > 1) ? 16 : 1][2][EPAD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid < 128) hist[tid >> 6][tid & 63] = 0;
     __syncthreads();
-    const scalar_t* x = static_cast<const scalar_t*>(p.x);
-    for (int i = wave; i < kRouteTokensPerBlock; i += 4) {
-        const int t = blockIdx.x * kRouteTokensPerBlock + i;
-        if (t < p.tokens) {
-            for (int g = 0; g < p.n_gates; ++g)
-                route_token<scalar_t, EPAD>(x + (size_t)t * p.hidden, p, p.gate[g], t, lane, hist[g]);
+    const int H = p.hidden, E = p.n_experts;
+    const int t = blockIdx.x * (16 / WPT) + wave / WPT;
+    const int slice = wave % WPT;
+    const bool live = t < p.tokens;
+    const scalar_t* xrow = static_cast<const scalar_t*>(p.x) + (size_t)(live ? t : 0) * H;
+    float acc[EPAD];
+    for (int g = 0; g < p.n_gates; ++g) {
+        if (live) {
+            gate_partial<scalar_t, EPAD>(xrow, static_cast<const scalar_t*>(p.gate[g].w), H, E, slice, WPT, lane, acc);
+            if (WPT == 1) {
+                select_topk<EPAD>(acc, p.gate[g], E, p.top_k, t, lane, hist[g]);
+            } else if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < EPAD; ++r) part[wave][g][r] = acc[r];
+            }
+        }
+    }
+    if (WPT > 1) {
+        __syncthreads();
+        if (live && slice == 0) {
+            for (int g = 0; g < p.n_gates; ++g) {
+#pragma unroll
+                for (int r = 0; r < EPAD; ++r) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int w = 0; w < WPT; ++w) s += part[wave + w][g][r];
+                    acc[r] = s;
+                }
+                select_topk<EPAD>(acc, p.gate[g], E, p.top_k, t, lane, hist[g]);
+            }
         }
     }
     __syncthreads();
-    if (tid < p.n_experts) {
-        for (int g = 0; g < p.n_gates; ++g)
-            if (p.gate[g].hist != nullptr) p.gate[g].hist[(size_t)blockIdx.x * p.n_experts + tid] = hist[g][tid];
+    if (tid < E) {
+        if (SMALL) {
+            if (p.counts != nullptr) p.counts[tid] = (p.accumulate ? p.counts[tid] : 0) + hist[0][tid];
+            if (p.counts_next != nullptr) p.counts_next[tid] = hist[1][tid];
+        } else {
+            for (int g = 0; g < p.n_gates; ++g)
+                if (p.gate[g].hist != nullptr) p.gate[g].hist[(size_t)blockIdx.x * E + tid] = hist[g][tid];
+        }
     }
 }
 
-// Decode path: every token of the call in one workgroup of 16 wavefronts; the
-// counts are final when the workgroup ends, so no second kernel is needed.
 template <typename scalar_t, int EPAD>
-__global__ __launch_bounds__(1024) void route_small_kernel(RouteParams p) {
-    __shared__ int hist[2][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 128) hist[tid >> 6][tid & 63] = 0;
-    __syncthreads();
-    const scalar_t* x = static_cast<const scalar_t*>(p.x);
-    for (int t = wave; t < p.tokens; t += 16) {
-        for (int g = 0; g < p.n_gates; ++g)
-            route_token<scalar_t, EPAD>(x + (size_t)t * p.hidden, p, p.gate[g], t, lane, hist[g]);
-    }
-    __syncthreads();
-    if (tid < p.n_experts) {
-        if (p.counts != nullptr) p.counts[tid] = (p.accumulate ? p.counts[tid] : 0) + hist[0][tid];
-        if (p.counts_next != nullptr) p.counts_next[tid] = hist[1][tid];
+void launch_epad(const RouteParams& p, bool small, hipStream_t stream) {
+    if (!small) {
+        route_kernel<scalar_t, EPAD, 1, false><<<route_blocks(p.tokens), 1024, 0, stream>>>(p);
+    } else if (p.tokens <= 1) {
+        route_kernel<scalar_t, EPAD, 16, true><<<1, 1024, 0, stream>>>(p);
+    } else if (p.tokens <= 2) {
+        route_kernel<scalar_t, EPAD, 8, true><<<1, 1024, 0, stream>>>(p);
+    } else if (p.tokens <= 4) {
+        route_kernel<scalar_t, EPAD, 4, true><<<1, 1024, 0, stream>>>(p);
+    } else if (p.tokens <= 8) {
+        route_kernel<scalar_t, EPAD, 2, true><<<1, 1024, 0, stream>>>(p);
+    } else {
+        route_kernel<scalar_t, EPAD, 1, true><<<1, 1024, 0, stream>>>(p);
     }
 }
 
 template <typename scalar_t>
 void launch_by_epad(const RouteParams& p, bool small, hipStream_t stream) {
     const int E = p.n_experts;
-    if (small) {
-        if (E <= 8) route_small_kernel<scalar_t, 8><<<1, 1024, 0, stream>>>(p);
-        else if (E <= 16) route_small_kernel<scalar_t, 16><<<1, 1024, 0, stream>>>(p);
-        else if (E <= 32) route_small_kernel<scalar_t, 32><<<1, 1024, 0, stream>>>(p);
-        else route_small_kernel<scalar_t, 64><<<1, 1024, 0, stream>>>(p);
-    } else {
-        const int nb = route_blocks(p.tokens);
-        if (E <= 8) route_kernel<scalar_t, 8><<<nb, 256, 0, stream>>>(p);
-        else if (E <= 16) route_kernel<scalar_t, 16><<<nb, 256, 0, stream>>>(p);
-        else if (E <= 32) route_kernel<scalar_t, 32><<<nb, 256, 0, stream>>>(p);
-        else route_kernel<scalar_t, 64><<<nb, 256, 0, stream>>>(p);
-    }
+    if (E <= 8) launch_epad<scalar_t, 8>(p, small, stream);
+    else if (E <= 16) launch_epad<scalar_t, 16>(p, small, stream);
+    else if (E <= 32) launch_epad<scalar_t, 32>(p, small, stream);
+    else launch_epad<scalar_t, 64>(p, small, stream);
 }
 
 RouteParams make_params(const moe_shape_t& s, int tokens, const void* x, const GateArgs* gates, int n_gates) {
