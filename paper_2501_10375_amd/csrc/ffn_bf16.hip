@@ -17,7 +17,7 @@ namespace {
 
 // Pipeline shape of the two GEMMs: K step and number of LDS stages (STAGES * 512 rows * BK * 2 bytes of LDS).
 constexpr int kBK = 32;
-constexpr int kStages = 5;
+constexpr int kStages = 4;
 constexpr int kWT = 2, kWW = 4;  // wavefront grid: slot groups x weight-row groups
 
 // y[t, :] = bf16( sum_j w[t, j] * out[slot_of[t, j], :] ), j ascending, fp32 sum, one rounding.
@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void combine_bf16(const float* __restrict__ ou
 hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w, const void* w1,
                            const void* w3, const void* w2, void* y, const int32_t* offs,
                            const int32_t* row_of_slot, const int32_t* slot_of, void* act, float* out,
-                           int32_t* sync, hipStream_t stream) {
+                           int32_t* sync, float* partial, hipStream_t stream) {
+    static_assert(gg::kSyncInts == kGemmSyncInts && gg::kScratchBytes == kGemmScratchBytes, "workspace layout");
     using G1 = gg::Gemm<2, kBK, kStages, kWT, kWW>;
     using G2 = gg::Gemm<1, kBK, kStages, kWT, kWW>;
     auto k1 = gg::grouped_gemm_kernel<2, kBK, kStages, kWT, kWW>;
@@ -70,11 +71,11 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
     const int grid = max(gg::kXcds, compute_units() / gg::kXcds * gg::kXcds);
     k1<<<grid, G1::kThreads, G1::kLdsBytes, stream>>>(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w1),
                                                       static_cast<const uint16_t*>(w3), offs, row_of_slot, s.n_experts,
-                                                      s.top_k, s.ffn, s.hidden, act, sync);
+                                                      s.top_k, s.ffn, s.hidden, act, sync, partial);
     stage_mark(stream, kStageGemm1);
     k2<<<grid, G2::kThreads, G2::kLdsBytes, stream>>>(static_cast<const uint16_t*>(act), static_cast<const uint16_t*>(w2),
                                                       nullptr, offs, row_of_slot, s.n_experts, s.top_k, s.hidden, s.ffn,
-                                                      out, sync + gg::kXcds);
+                                                      out, sync + gg::kSyncInts, partial);
     stage_mark(stream, kStageGemm2);
     combine_bf16<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, static_cast<uint16_t*>(y));
     stage_mark(stream, kStageCombine);

@@ -1,27 +1,28 @@
 // Grouped bf16 GEMM for the expert FFN on the CDNA4 matrix cores (device code).
 //
-// Computes, for one (expert, 256-slot tile, feature tile) per workgroup,
+// Computes, per (expert, 256-slot tile, feature tile),
 //   NMAT = 2 (gemm1): act[slot, f] = silu(tok[slot] . wa[e, f]) * (tok[slot] . wb[e, f])   (bf16 out)
 //   NMAT = 1 (gemm2): out[slot, n] = tok[slot] . wa[e, n]                                  (fp32 out)
 // where tok rows are gathered rows of x (gemm1) or rows of act (gemm2), and every
 // operand is K-contiguous ("row . row" contraction, no transposes anywhere).
 //
 // Organisation (gfx950):
-//   * Workgroup tile 256 slots x 256 weight rows (NMAT = 2: 128 features of each
-//     matrix), K in steps of BK.  WT x WW wavefronts (slot groups x weight-row
-//     groups); each owns (256/WT) x (256/WW) outputs as v_mfma_f32_32x32x16_bf16
-//     tiles.  Weights are the MFMA "A" operand, slot rows the "B" operand, so a
-//     lane ends up holding 4 consecutive output features of one slot.
-//   * Operand tiles go HBM/L2 -> LDS directly (global_load_lds_dwordx4, no
-//     register staging), STAGES tiles deep.  Each lane supplies its own global
-//     address, which is how gathered rows and the XOR swizzle are expressed: the
-//     16-byte piece that must land at LDS position p is fetched by the lane
-//     whose data lands at p.  The swizzle makes the ds_read_b128 operand reads
-//     bank-conflict free.
-//   * The loads are issued from inline asm so the compiler does not serialise
-//     them against the LDS reads of other stages; completion is enforced by hand:
-//     s_waitcnt vmcnt(n) on the issuing wavefront, then a workgroup barrier,
-//     before any wavefront reads the stage.  One barrier per K step.
+//   * Tile 256 slots x 256 weight rows (NMAT = 2: 128 features of each matrix), K in steps of BK.
+//     WT x WW wavefronts (slot groups x weight-row groups); each owns (256/WT) x (256/WW) outputs
+//     as v_mfma_f32_32x32x16_bf16 tiles.  Weights are the MFMA "A" operand, slot rows the "B"
+//     operand, so a lane ends up holding 4 consecutive output features of one slot.
+//   * Operand tiles go HBM/L2 -> LDS directly (global_load_lds_dwordx4, no register staging), in a
+//     ring of STAGES tiles.  Each lane supplies its own global address, which is how gathered rows
+//     and the XOR swizzle are expressed: the 16-byte piece that must land at LDS position p is
+//     fetched by the lane whose data lands at p.  The swizzle makes the ds_read_b128 operand reads
+//     bank-conflict free on the 64-bank LDS.
+//   * The loads are issued from inline asm so the compiler does not serialise them against the
+//     LDS reads of other stages; completion is enforced by hand: s_waitcnt vmcnt(n) on the issuing
+//     wavefront, then a workgroup barrier, before any wavefront reads the stage.  One barrier per
+//     K step.  Inside a step MFMAs, LDS reads and loads are interleaved one for one.
+//   * Persistent schedule, one workgroup per CU, tiles handed out in XCD-synchronous rounds so the
+//     workgroups of an XCD share operand tiles through its L2; the last, partial round is split
+//     along K so that all CUs stay busy (see persistent()).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -39,17 +40,26 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kBT = 256;      // slots per workgroup tile
-constexpr int kBW = 256;      // weight rows per workgroup tile (all matrices together)
+constexpr int kBT = 256;   // slots per tile
+constexpr int kBW = 256;   // weight rows per tile (all matrices together)
 constexpr int kXcds = 8;
+constexpr int kMaxWgsPerXcd = 32;  // persistent grid: at most 8 x 32 workgroups
+constexpr int kMaxSplit = 8;       // K parts of a tile in the last round
+
+// Layout of the int32 `sync` block a GEMM launch uses (all zero when the kernel starts):
+//   [0, 8)                      rendezvous counter of each XCD
+//   [8, 8 + 8 * 32)             arrival counter of each split tile (XCD-major)
+constexpr int kSyncInts = kXcds + kXcds * kMaxWgsPerXcd;
+// fp32 scratch for split tiles: one 256 x 256 partial accumulator tile per workgroup.
+constexpr size_t kPartialFloats = (size_t)kBT * kBW;
+constexpr size_t kScratchBytes = (size_t)kXcds * kMaxWgsPerXcd * kPartialFloats * sizeof(float);
 
 // Tile list.  The number of real tiles depends on the routing (sum over experts of
 // ceil(count / 256) slot tiles, times the feature tiles) and is only known on the device, so
 // every workgroup derives it from `offs`.  Tile order: expert, group of kGroup slot tiles, feature
 // tile, slot tile within the group.  32 consecutive tiles (what the 32 CUs of one XCD work on at
 // one time) are then about 8 slot tiles x 4 feature tiles of one expert: 12 distinct operand tiles
-// feed 32 workgroups through the XCD's L2, which is what keeps traffic from HBM and the
-// memory-side cache near its minimum.
+// feed 32 workgroups through the XCD's L2.
 constexpr int kGroup = 8;
 
 __device__ inline int count_tiles(const int32_t* __restrict__ offs, int E, int n_ftiles) {
@@ -131,11 +141,7 @@ struct Swz<32> {  // 64-byte rows, 4 pieces; four rows span the 64 banks
     static __device__ inline int piece(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 };
 
-#ifdef MOE_GEMM_CLOCK_PROBE
-__device__ long long g_clock_probe[24];
-#endif
-
-template <int NMAT, int BK, int STAGES, int WT, int WW, int DBG = 0>
+template <int NMAT, int BK, int STAGES, int WT, int WW>
 struct Gemm {
     static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
     static constexpr int kThreads = kWaves * 64;
@@ -153,47 +159,66 @@ struct Gemm {
     static constexpr int kPieces = kRowBytes / 16;
     static constexpr int kKSteps = BK / 16;
     static constexpr int kBF = kBW / NMAT;                     // features per tile (per matrix)
+    static constexpr int kFragsPerMat = kWF / NMAT;
+    static constexpr int kFeatPerWave = 32 * kFragsPerMat;
+    static_assert(kLdsBytes >= 65536, "the epilogue transposes 64 KB through LDS");
 
     // tok_base: gemm1 -> x [T, K] rows gathered via row_of_slot / topk; gemm2 -> act [A, K] rows = slots.
     // wa, wb: [E, N, K]; dst: gemm1 -> bf16 [A, N]; gemm2 -> fp32 [A, N].
+    //
     // Persistent schedule: the grid is one workgroup per CU.  Workgroup b belongs to XCD b % 8 (the
     // hardware deals workgroups round-robin to the XCDs) and is its member b / 8.  Each XCD owns one
-    // contiguous eighth of the tile list and works through it in rounds of `wgs_per_xcd` consecutive
+    // contiguous eighth of the tile list and works through it in rounds of `members` consecutive
     // tiles, one per member.  Before each new round the members meet (xcd_rendezvous), so they walk
     // K in step and every operand line is pulled into the XCD's L2 once per round instead of once
-    // per workgroup.  `sync` points at 8 counters that are zero when the kernel starts.
+    // per workgroup.
+    //
+    // The last round usually has fewer tiles than members (`rem`).  Each of its tiles is then split
+    // along K into `parts` = min(kMaxSplit, members / rem) pieces computed by different members.
+    // Every piece is written to `scratch` as a raw accumulator tile; the member that arrives last at
+    // the tile's counter adds the pieces in part order (so the result does not depend on who that
+    // is) and runs the normal epilogue.
     static __device__ void persistent(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
                                       const uint16_t* __restrict__ wb, const int32_t* __restrict__ offs,
                                       const int32_t* __restrict__ row_of_slot, int E, int topk, int N, int K,
-                                      void* __restrict__ dst, int32_t* __restrict__ sync, unsigned char* lds) {
+                                      void* __restrict__ dst, int32_t* __restrict__ sync,
+                                      float* __restrict__ scratch, unsigned char* lds) {
         const int n_ftiles = (N + kBF - 1) / kBF;
         const int total = count_tiles(offs, E, n_ftiles);
-        const int xcd = blockIdx.x % kXcds, member = blockIdx.x / kXcds, wgs_per_xcd = gridDim.x / kXcds;
+        const int KT = K / BK;
+        const int xcd = blockIdx.x % kXcds, member = blockIdx.x / kXcds;
+        const int members = min((int)gridDim.x / kXcds, kMaxWgsPerXcd);
+        if (member >= members) return;
         const int chunk = (total + kXcds - 1) / kXcds;
         const int first = xcd * chunk, last = min(total, first + chunk);
-        const int rounds = (max(last - first, 0) + wgs_per_xcd - 1) / wgs_per_xcd;
+        const int len = max(last - first, 0);
+        const int full_rounds = len / members, rem = len - full_rounds * members;
+        const int parts = rem > 0 ? max(1, min(min(kMaxSplit, members / rem), KT / STAGES)) : 1;
+        const int rounds = full_rounds + (rem > 0 ? 1 : 0);
         for (int r = 0; r < rounds; ++r) {
-            if (r > 0) xcd_rendezvous(sync + xcd, r * wgs_per_xcd);
-            const int id = first + r * wgs_per_xcd + member;
-            if (id < last) {
-                int e, slot0, rows, ft;
-                tile_of(offs, E, n_ftiles, id, e, slot0, rows, ft);
-                if (DBG & 4) { e = 0; slot0 = 0; rows = 256; ft = 0; }  // probe: every tile reads the same operands
-                tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft);
-            }
+            if (r > 0) xcd_rendezvous(sync + xcd, r * members);
+            const bool split = r == full_rounds;  // the last, partial round
+            const int p = split ? parts : 1;
+            if (split && member >= rem * p) break;
+            const int t = member / p, part = member - t * p;
+            int e, slot0, rows, ft;
+            tile_of(offs, E, n_ftiles, first + r * members + t, e, slot0, rows, ft);
+            const int kt0 = (int)((long)KT * part / p), kt1 = (int)((long)KT * (part + 1) / p);
+            tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft, kt0, kt1, p, part,
+                 scratch + ((size_t)xcd * kMaxWgsPerXcd + (size_t)t * p) * kPartialFloats,
+                 sync + kXcds + xcd * kMaxWgsPerXcd + t);
         }
     }
 
+    // One tile over K steps [kt_begin, kt_end).  parts == 1: a whole tile.  parts > 1: piece `part`
+    // of a split tile; `partials` is where this tile's pieces live (piece p at p * kPartialFloats),
+    // `arrivals` its zero-initialised counter.
     static __device__ void tile(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
                                 const uint16_t* __restrict__ wb, const int32_t* __restrict__ row_of_slot, int topk,
                                 int N, int K, void* __restrict__ dst, unsigned char* lds, int e, int slot0, int rows,
-                                int ft) {
+                                int ft, int kt_begin, int kt_end, int parts, int part, float* __restrict__ partials,
+                                int32_t* __restrict__ arrivals) {
         const int n0 = ft * kBF;
-#ifdef MOE_GEMM_CLOCK_PROBE
-        const long long probe_c0 = __builtin_readcyclecounter(), probe_w0 = wall_clock64();
-        long long probe_w1 = 0;
-#endif
-
         const int tid = threadIdx.x, lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
         const int wt = wave % WT, wq = wave / WT;  // slot group, weight-row group
@@ -202,6 +227,7 @@ struct Gemm {
         // ---- staging addresses: this wavefront stages rows [wave, wave + 1) * kStageRows of each operand
         const int lrow = lane / kPieces;                       // row within a 1 KB load
         const int lpiece = lane % kPieces;                     // LDS piece position within the row
+        const size_t k_first = (size_t)kt_begin * kRowBytes;   // byte offset of this piece's first K step
         const char* gp[kLoads];
 #pragma unroll
         for (int q = 0; q < kLoadsPerOperand; ++q) {
@@ -209,19 +235,19 @@ struct Gemm {
             const int chunk = Swz<BK>::piece(r, lpiece);        // global piece that belongs at this position
             const int slot = slot0 + min(r, rows - 1);          // rows past the end re-read the last valid row
             const int src = (NMAT == 2) ? row_of_slot[slot] / topk : slot;
-            gp[q] = reinterpret_cast<const char*>(tok_base + (size_t)src * K) + chunk * 16;
+            gp[q] = reinterpret_cast<const char*>(tok_base + (size_t)src * K) + chunk * 16 + k_first;
             // weight rows: NMAT == 2 -> rows 0..127 are wa features, 128..255 wb features
             const int mat = (NMAT == 2) ? (r >> 7) : 0;
             const int f = min(n0 + ((NMAT == 2) ? (r & 127) : r), N - 1);
             const uint16_t* wsrc = (mat == 0) ? wa : wb;
-            gp[kLoadsPerOperand + q] = reinterpret_cast<const char*>(wsrc + ((size_t)e * N + f) * K) + chunk * 16;
+            gp[kLoadsPerOperand + q] = reinterpret_cast<const char*>(wsrc + ((size_t)e * N + f) * K) + chunk * 16 + k_first;
         }
-        const int KT = K / BK;
+        const int KT = kt_end - kt_begin;  // K steps of this piece, numbered from 0 below
         const uint32_t stage_off_tok = (uint32_t)(wave * kStageRows * kRowBytes);
         const uint32_t stage_off_w = (uint32_t)(kTileBytes + wave * kStageRows * kRowBytes);
 
-        // The loads of one stage are issued in kKSteps parts, one per k16 step of the tile being
-        // computed, and within a step one at a time between MFMAs (see step() below).
+        // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
+        // computed, and within a k16 step one at a time between MFMAs (see step() below).
         static_assert(kLoads % kKSteps == 0, "loads per stage must split evenly over the k16 steps");
         constexpr int kLoadsPerPart = kLoads / kKSteps;
         auto dma_one = [&](int stage, int kt, int l) {
@@ -238,12 +264,11 @@ struct Gemm {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-        // ---- operand read offsets (bytes within an operand tile), per k16 step
+        // ---- operand read offsets (rows within an operand tile)
         const int frow = lane & 31, fhalf = lane >> 5;
-        // Weight frag j: NMAT == 2 -> matrix j / (kWF/2), feature tile j % (kWF/2) of this wavefront's
-        // features [wq * kFeatPerWave, +kFeatPerWave); NMAT == 1 -> weight rows wq * 32 * kWF + 32 j.
-        constexpr int kFragsPerMat = kWF / NMAT;
-        constexpr int kFeatPerWave = 32 * kFragsPerMat;
+        // Weight frag j: NMAT == 2 -> matrix j / kFragsPerMat, feature tile j % kFragsPerMat of this
+        // wavefront's features [wq * kFeatPerWave, +kFeatPerWave); NMAT == 1 -> weight rows
+        // wq * kFeatPerWave + 32 j.
         int trow[kTF], wrow[kWF];
 #pragma unroll
         for (int i = 0; i < kTF; ++i) trow[i] = wt * (32 * kTF) + i * 32 + frow;
@@ -254,10 +279,10 @@ struct Gemm {
         // Operand fragments are double-buffered in registers (buffer = k16 step & 1).  One pipeline
         // step issues the MFMAs of one k16 step and, BETWEEN them one for one, the LDS reads of the
         // next step's fragments (into the other buffer) and this wavefront's share of the global->LDS
-        // loads of a later tile.  Interleaving matters: a burst of ds_reads from all wavefronts right
+        // loads of a later K step.  Interleaving matters: a burst of ds_reads from all wavefronts right
         // after a barrier fills the LDS command queue and blocks the issuing wavefronts, MFMAs
         // included; one read per MFMA keeps the matrix pipe fed while the queue drains.  The MFMAs of a
-        // tile's LAST step run after the next tile's barrier, paired with that tile's first reads, so
+        // K step's LAST k16 step run after the next K step's barrier, paired with its first reads, so
         // the matrix pipe also has work while the wavefronts re-synchronise.
         static_assert(kKSteps % 2 == 0, "fragment buffers alternate per k16 step");
         constexpr int kM = kWF * kTF, kR = kWF + kTF;
@@ -272,18 +297,17 @@ struct Gemm {
                 tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
                     st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
         };
-        constexpr bool kCompute = (DBG & 3) != 2, kStream = (DBG & 3) != 1;
         // mfma: issue the MFMAs of buffer mbuf.  read: fetch fragments (rstage, rks) into buffer rbuf.
-        // dma: issue part dpart of tile dkt's loads into stage dstage.
+        // dma: issue part dpart of K step dkt's loads into stage dstage.
         auto step = [&](auto mfma, int mbuf, auto read, int rstage, int rks, int rbuf, bool dma, int dstage, int dkt,
                         int dpart) {
 #pragma unroll
             for (int m = 0; m < kM; ++m) {
-                if (decltype(mfma)::value && kCompute) {
+                if (decltype(mfma)::value) {
                     const int i = m / kWF, j = m % kWF;
                     acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
                 }
-                if (decltype(read)::value && kCompute && m < kR) read_one(rstage, rks, rbuf, m);
+                if (decltype(read)::value && m < kR) read_one(rstage, rks, rbuf, m);
                 if (m >= kM - kLoadsPerPart && dma) dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -291,7 +315,7 @@ struct Gemm {
         using Yes = std::true_type;
         using No = std::false_type;
 
-        // prologue: STAGES - 1 tiles in flight
+        // prologue: STAGES - 1 K steps in flight
 #pragma unroll
         for (int s = 0; s < STAGES - 1; ++s)
             if (s < KT) {
@@ -303,16 +327,13 @@ struct Gemm {
             for (int s = 0; s < STAGES; ++s) {
                 const int kt = kt0 + s;
                 if (kt < KT) {
-                    // tile kt must have landed; up to STAGES - 2 younger tiles may stay in flight
+                    // K step kt must have landed; up to STAGES - 2 younger ones may stay in flight
                     if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * kLoads>();
                     else wait_vmcnt<0>();
                     lds_barrier();
-#ifdef MOE_GEMM_CLOCK_PROBE
-                    if (kt == 0) probe_w1 = wall_clock64();
-#endif
-                    const bool more = kt + STAGES - 1 < KT && kStream;
+                    const bool more = kt + STAGES - 1 < KT;
                     const int ns = (s + STAGES - 1) % STAGES;
-                    // last step of tile kt - 1 (buffer 1) with the first reads of tile kt (buffer 0)
+                    // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
                     if (kt > 0) step(Yes{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
                     else step(No{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
 #pragma unroll
@@ -323,9 +344,51 @@ struct Gemm {
         }
         step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, 0);
 
-#ifdef MOE_GEMM_CLOCK_PROBE
-        const long long probe_c2 = __builtin_readcyclecounter(), probe_w2 = wall_clock64();
-#endif
+        // ---- split tiles: publish this piece; the last piece to arrive sums them all in part order.
+        if (parts > 1) {
+            float* mine = partials + (size_t)part * kPartialFloats;
+#pragma unroll
+            for (int j = 0; j < kWF; ++j)
+#pragma unroll
+                for (int i = 0; i < kTF; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 v;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[c] = acc[j][i][q * 4 + c];
+                        *reinterpret_cast<f32x4*>(mine + ((size_t)((j * kTF + i) * 4 + q) * kThreads + tid) * 4) = v;
+                    }
+            __threadfence();  // the piece is visible device-wide before the arrival is counted
+            __syncthreads();
+            int* flag = reinterpret_cast<int*>(lds);
+            if (tid == 0) *flag = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const bool is_last = *flag == parts - 1;
+            __syncthreads();  // everyone has read the flag before LDS is reused
+            if (!is_last) return;  // only ever in the last round, so nothing follows for this workgroup
+            __threadfence();  // the other pieces are visible before they are read
+#pragma unroll
+            for (int j = 0; j < kWF; ++j)
+#pragma unroll
+                for (int i = 0; i < kTF; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+            for (int p = 0; p < parts; ++p) {
+                const float* src = partials + (size_t)p * kPartialFloats;
+#pragma unroll
+                for (int j = 0; j < kWF; ++j)
+#pragma unroll
+                    for (int i = 0; i < kTF; ++i)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v =
+                                *reinterpret_cast<const f32x4*>(src + ((size_t)((j * kTF + i) * 4 + q) * kThreads + tid) * 4);
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) acc[j][i][q * 4 + c] += v[c];
+                        }
+            }
+        }
+
         // ---- epilogue: transpose through LDS so that global stores are whole contiguous rows.
         // MFMA 32x32 result: lane holds column (slot) lane & 31 and rows (weight rows)
         // 8 * (r / 4) + 4 * (lane / 32) + (r % 4), r = 0..15, i.e. 4 consecutive features per r / 4.
@@ -390,27 +453,21 @@ struct Gemm {
                 }
             }
         }
-#ifdef MOE_GEMM_CLOCK_PROBE
-        if (blockIdx.x == 100 && threadIdx.x == 0) {
-            g_clock_probe[0] = probe_c2 - probe_c0;
-            g_clock_probe[1] = probe_w2 - probe_w0;
-            g_clock_probe[2] = probe_w1 - probe_w0;       // setup + first tile landed
-            g_clock_probe[3] = wall_clock64() - probe_w2;  // epilogue
-        }
-#endif
     }
 };
 
-template <int NMAT, int BK, int STAGES, int WT, int WW, int DBG = 0>
+template <int NMAT, int BK, int STAGES, int WT, int WW>
 __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uint16_t* __restrict__ tok_base,
                                                                     const uint16_t* __restrict__ wa,
                                                                     const uint16_t* __restrict__ wb,
                                                                     const int32_t* __restrict__ offs,
                                                                     const int32_t* __restrict__ row_of_slot, int E,
                                                                     int topk, int N, int K, void* __restrict__ dst,
-                                                                    int32_t* __restrict__ sync) {
+                                                                    int32_t* __restrict__ sync,
+                                                                    float* __restrict__ scratch) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
-    Gemm<NMAT, BK, STAGES, WT, WW, DBG>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, lds_dyn);
+    Gemm<NMAT, BK, STAGES, WT, WW>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
+                                               lds_dyn);
 }
 
 }  // namespace gg

@@ -21,6 +21,8 @@ WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
     L.route_end = off;
     L.act = off;         off = align_up(off + A * (size_t)s.ffn * esz);
     L.out = off;         off = align_up(off + A * (size_t)s.hidden * sizeof(float));
+    L.partial = off;
+    if (s.dtype == MOE_BF16 && tokens > kDecodeMaxTokens) off = align_up(off + kGemmScratchBytes);
     L.total = off;
     return L;
 }
@@ -114,6 +116,7 @@ struct Ws {
     int32_t *hist, *hist_next, *offs, *row_of_slot, *slot_of, *sync;
     void* act;
     float* out;
+    float* partial;
 };
 
 Ws carve(void* workspace, const WorkspaceLayout& L) {
@@ -127,6 +130,7 @@ Ws carve(void* workspace, const WorkspaceLayout& L) {
     w.sync = reinterpret_cast<int32_t*>(b + L.sync);
     w.act = b + L.act;
     w.out = reinterpret_cast<float*>(b + L.out);
+    w.partial = reinterpret_cast<float*>(b + L.partial);
     return w;
 }
 
@@ -168,7 +172,7 @@ hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_
                               static_cast<const float*>(w3), static_cast<const float*>(w2), static_cast<float*>(y),
                               ws.offs, ws.row_of_slot, ws.slot_of, static_cast<float*>(ws.act), ws.out, stream);
     return launch_ffn_bf16(s, tokens, x, w, w1, w3, w2, y, ws.offs, ws.row_of_slot, ws.slot_of, ws.act, ws.out,
-                           ws.sync, stream);
+                           ws.sync, ws.partial, stream);
 }
 
 }  // namespace

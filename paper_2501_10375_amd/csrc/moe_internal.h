@@ -27,10 +27,11 @@ struct WorkspaceLayout {
     size_t offs;         // int32 [E + 1]        exclusive scan of counts
     size_t row_of_slot;  // int32 [A]            slot -> assignment index t*k + j
     size_t slot_of;      // int32 [A]            assignment index -> slot
-    size_t sync;         // int32 [16]           rendezvous counters of the two grouped GEMMs
+    size_t sync;         // int32 [kSyncInts]    rendezvous / arrival counters of the two grouped GEMMs
     size_t route_end;    // bytes needed by routing-only calls
     size_t act;          // dtype [A, F]         silu(W1 x) * (W3 x)
     size_t out;          // fp32  [A, H]         per-assignment expert output
+    size_t partial;      // fp32  [8 * 32, 256, 256]  pieces of K-split tiles (bf16 prefill path only)
     size_t total;        // bytes needed by the whole layer
 };
 
@@ -68,8 +69,12 @@ hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t*
 // Sum block histograms into counts (counts may be null), and when
 // row_of_slot/slot_of are given build offs and the stable token->expert
 // permutation.
+// Counters and scratch of the persistent grouped GEMMs (see grouped_gemm_bf16.h): per launch 8 XCD
+// rendezvous counters + 8 x 32 split-tile arrival counters, and one 256 x 256 fp32 piece per workgroup.
+constexpr int kGemmSyncInts = 8 + 8 * 32;
+constexpr int kSyncInts = 2 * kGemmSyncInts;  // gemm1 and gemm2
+constexpr size_t kGemmScratchBytes = (size_t)8 * 32 * 256 * 256 * sizeof(float);
 // `sync` (may be null) is a block of kSyncInts counters that is cleared for the GEMMs that follow.
-constexpr int kSyncInts = 16;
 hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
                            int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
                            int32_t* slot_of, int32_t* sync, hipStream_t stream);
@@ -90,7 +95,7 @@ hipError_t launch_ffn_f32(const moe_shape_t& s, int tokens, const float* x, cons
 hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w,
                            const void* w1, const void* w3, const void* w2, void* y,
                            const int32_t* offs, const int32_t* row_of_slot, const int32_t* slot_of,
-                           void* act, float* out, int32_t* sync, hipStream_t stream);
+                           void* act, float* out, int32_t* sync, float* partial, hipStream_t stream);
 
 // Number of compute units of the current device (cached per device).
 int compute_units();

@@ -74,7 +74,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(const int32_t* __restrict
         if (blk == 0 && offs != nullptr) offs[E] = run;
     }
     if (blk == 0 && counts != nullptr && tid < E) counts[tid] = (accumulate ? counts[tid] : 0) + total[tid];
-    if (blk == 0 && sync != nullptr && tid < kSyncInts) sync[tid] = 0;
+    if (blk == 0 && sync != nullptr)
+        for (int i = tid; i < kSyncInts; i += 256) sync[i] = 0;
     if (row_of_slot == nullptr) return;
     const int a0 = blk * kRouteTokensPerBlock * k;
     const int n_local = min(tokens * k, a0 + kRouteTokensPerBlock * k) - a0;
