@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--decode-layers", type=int, default=4,
                     help="distinct weight sets the decode loop rotates over (keeps the weights cold in cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run a plain device-to-device copy of this many MiB three times (reference for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle is timed on (0 = pick for ~15 s)")
     return ap.parse_args()
 
@@ -88,6 +91,16 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
+
+    if args.copy_calibration > 0:
+        n = args.copy_calibration << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "copies": 3}))
+        return
     from paper_2501_10375_amd import moe, synth
 
     moe.lib()

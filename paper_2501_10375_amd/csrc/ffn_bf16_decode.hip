@@ -32,6 +32,14 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// Pipeline depths (k32 steps of loads in flight per wavefront) of the two kernels.
+#ifndef MOE_DEC_P1
+#define MOE_DEC_P1 8
+#endif
+#ifndef MOE_DEC_P2
+#define MOE_DEC_P2 16
+#endif
+
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kMaxTok = kDecodeMaxTokens;
@@ -266,12 +274,12 @@ hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* 
                                   void* act, hipStream_t stream) {
     const int max_tiles = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
     const int grid1 = min(compute_units(), max_tiles);
-    dec_gemm1<8><<<grid1, kThreads, 0, stream>>>(static_cast<const uint16_t*>(x), topk_idx,
+    dec_gemm1<MOE_DEC_P1><<<grid1, kThreads, 0, stream>>>(static_cast<const uint16_t*>(x), topk_idx,
                                                  static_cast<const uint16_t*>(w1), static_cast<const uint16_t*>(w3),
                                                  tokens, s.top_k, s.n_experts, s.hidden, s.ffn,
                                                  static_cast<uint16_t*>(act));
     stage_mark(stream, kStageGemm1);
-    dec_gemm2<16><<<s.hidden / 16, kThreads, 0, stream>>>(static_cast<const uint16_t*>(act), topk_idx, topk_w,
+    dec_gemm2<MOE_DEC_P2><<<s.hidden / 16, kThreads, 0, stream>>>(static_cast<const uint16_t*>(act), topk_idx, topk_w,
                                                           static_cast<const uint16_t*>(w2), tokens, s.top_k,
                                                           s.n_experts, s.hidden, s.ffn, static_cast<uint16_t*>(y));
     stage_mark(stream, kStageGemm2);
