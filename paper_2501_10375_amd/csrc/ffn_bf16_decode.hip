@@ -8,13 +8,25 @@
 //
 //   * no permutation and no LDS staging of weights: every weight byte is used
 //     by exactly one wavefront, so it is loaded straight into MFMA operand
-//     registers with 16-byte loads (16 rows x 64 contiguous bytes per load);
-//   * the tokens of an expert form the 16 columns of a v_mfma_f32_16x16x32_bf16,
-//     so up to 16 tokens share one pass over the weights; lanes whose column
-//     has no token issue no load;
+//     registers with 16-byte loads;
+//   * every load instruction covers 8 weight rows x 128 contiguous bytes (whole
+//     cache lines; 64-byte pieces stream measurably slower).  The natural
+//     operand layout of v_mfma_f32_16x16x32_bf16 would give 16 rows x 64 bytes,
+//     so the 16 operand rows are used as 8 weight rows x 2 halves of a 64-wide
+//     K step instead: a second load fetches the next 8 weight rows with the
+//     halves swapped, a per-lane select recombines the two loads into one
+//     operand holding the lower K half of all 16 weight rows and one holding
+//     the upper half (with rows i and i ^ 8 exchanged), and two MFMAs with the
+//     matching halves of the tokens accumulate them; the two accumulators are
+//     added, after undoing the row exchange with a cross-lane move, when the
+//     tile is finished;
+//   * the tokens of an expert form the 16 columns of the MFMA, so up to 16
+//     tokens share one pass over the weights; lanes whose column has no token
+//     issue no load;
 //   * each wavefront keeps P steps of loads in flight in a rotating register
 //     window (software pipeline unrolled P times) that runs across tile
-//     boundaries, so the stream never drains;
+//     boundaries, and the barrier at a tile's end waits for LDS only, so the
+//     stream never drains;
 //   * the 8 wavefronts of a workgroup split K, and their partial 16 x 16 tiles
 //     are summed through LDS in a fixed order (deterministic);
 //   * the token groups are rebuilt by every workgroup from topk_idx (at most
@@ -34,10 +46,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // Pipeline depths (k32 steps of loads in flight per wavefront) of the two kernels.
 #ifndef MOE_DEC_P1
-#define MOE_DEC_P1 8
+#define MOE_DEC_P1 4
 #endif
 #ifndef MOE_DEC_P2
-#define MOE_DEC_P2 16
+#define MOE_DEC_P2 8
 #endif
 
 constexpr int kWaves = 8;
@@ -79,16 +91,53 @@ __device__ void build_groups(Groups& g, const int32_t* __restrict__ idx, int A, 
     __syncthreads();
 }
 
-__device__ inline bf16x8 load_frag(const uint16_t* p, bool on) {
-    bf16x8 v;
-    if (on) {
-        v = *reinterpret_cast<const bf16x8*>(p);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (__bf16)0.f;
-    }
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ inline u32x4 load16(const uint16_t* p, bool on) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (on) v = *reinterpret_cast<const u32x4*>(p);
     return v;
 }
+
+__device__ inline bf16x8 pick(bool first, u32x4 a, u32x4 b) {
+    u32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = first ? a[i] : b[i];
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// Barrier that orders LDS traffic only: loads from global memory stay in flight across it.
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// acc1 holds MFMA row i = weight row i, acc2 holds MFMA row i = weight row i ^ 8; MFMA rows
+// 4 * (lane / 16) + r sit in lane, so row i ^ 8 is the same register of lane ^ 32.
+__device__ inline f32x4 fold_halves(f32x4 acc1, f32x4 acc2) {
+    f32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = acc1[i] + __shfl_xor(acc2[i], 32, 64);
+    return r;
+}
+
+// Per-lane element offsets inside a tile of 16 weight rows and a 64-element K step.
+struct LaneMap {
+    int row_lo, row_hi;  // weight rows (within the tile) of the two loads
+    int k_lo, k_hi;      // element offset of this lane's 8 elements inside the K step
+    int kq8;             // element offset of the lane's token operand inside each 32-element half
+    bool upper;
+    __device__ explicit LaneMap(int lane) {
+        const int i = lane & 15, kq = lane >> 4;
+        upper = i >= 8;
+        row_lo = i & 7;
+        row_hi = 8 + (i & 7);
+        k_lo = ((upper ? 4 : 0) + kq) * 8;
+        k_hi = ((upper ? 0 : 4) + kq) * 8;
+        kq8 = kq * 8;
+    }
+};
 
 template <int P>
 __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict__ x,
@@ -100,7 +149,8 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
     __shared__ f32x4 red[2][kWaves][2][64];
     build_groups(g, idx, T * k, E);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int col = lane & 15, kq = lane >> 4;
+    const int col = lane & 15;
+    const LaneMap lm(lane);
 
     const int tiles_per_expert = F / 16;
     const int total_tiles = g.n_active * tiles_per_expert;
@@ -109,33 +159,38 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
     const int t1 = min(total_tiles, t0 + tiles_per_wg);
     if (t0 >= t1) return;
 
-    // K split: 32-element steps dealt to the wavefronts in contiguous runs.
-    const int k_steps = H / 32;
+    // K split: 64-element steps dealt to the wavefronts in contiguous runs.
+    const int k_steps = H / 64;
     const int per = (k_steps + kWaves - 1) / kWaves;
     const int s_begin = wave * per;
     const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
     const int spt = (per + P - 1) / P * P;  // steps per tile, padded to the pipeline depth
     const long total_q = (long)(t1 - t0) * spt;
 
-    bf16x8 fw1[P], fw3[P], fx[P];
+    u32x4 lo1[P], hi1[P], lo3[P], hi3[P], xa[P], xb[P];
     // Issue-side state: the next step to request and the row bases of its tile.
     int is = 0, itile = t0;
-    size_t wbase = 0, xbase = 0;
+    size_t wlo = 0, whi = 0, xbase = 0;
     bool xcol = false;
     auto enter_tile = [&]() {
         const int d = itile / tiles_per_expert;
         const int f0 = (itile - d * tiles_per_expert) * 16;
-        const size_t koff = (size_t)s_begin * 32 + kq * 8;
-        wbase = ((size_t)g.expert[d] * F + f0 + col) * H + koff;
+        const size_t row0 = (size_t)g.expert[d] * F + f0;
+        const size_t k0 = (size_t)s_begin * 64;
+        wlo = (row0 + lm.row_lo) * H + k0 + lm.k_lo;
+        whi = (row0 + lm.row_hi) * H + k0 + lm.k_hi;
         xcol = col < g.cnt[d];
-        xbase = (size_t)(xcol ? g.assign[d][col] / k : 0) * H + koff;
+        xbase = (size_t)(xcol ? g.assign[d][col] / k : 0) * H + k0 + lm.kq8;
     };
     enter_tile();
     auto issue = [&](int i) {
         const bool on = is < n_valid;
-        fw1[i] = load_frag(w1 + wbase + is * 32, on);
-        fw3[i] = load_frag(w3 + wbase + is * 32, on);
-        fx[i] = load_frag(x + xbase + is * 32, on && xcol);
+        lo1[i] = load16(w1 + wlo + is * 64, on);
+        hi1[i] = load16(w1 + whi + is * 64, on);
+        lo3[i] = load16(w3 + wlo + is * 64, on);
+        hi3[i] = load16(w3 + whi + is * 64, on);
+        xa[i] = load16(x + xbase + is * 64, on && xcol);
+        xb[i] = load16(x + xbase + is * 64 + 32, on && xcol);
         if (++is == spt) {
             is = 0;
             if (++itile < t1) enter_tile();
@@ -144,13 +199,18 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
 #pragma unroll
     for (int i = 0; i < P; ++i) issue(i);  // total_q >= spt >= P
 
-    f32x4 accg = {0.f, 0.f, 0.f, 0.f}, accu = {0.f, 0.f, 0.f, 0.f};
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 g1 = zero, g2 = zero, u1 = zero, u2 = zero;
     int cs = 0, ctile = t0;
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            accg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw1[i], fx[i], accg, 0, 0, 0);
-            accu = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw3[i], fx[i], accu, 0, 0, 0);
+            const bf16x8 b1 = __builtin_bit_cast(bf16x8, xa[i]);
+            const bf16x8 b2 = __builtin_bit_cast(bf16x8, xb[i]);
+            g1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, hi1[i], lo1[i]), b1, g1, 0, 0, 0);
+            g2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo1[i], hi1[i]), b2, g2, 0, 0, 0);
+            u1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, hi3[i], lo3[i]), b1, u1, 0, 0, 0);
+            u2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo3[i], hi3[i]), b2, u2, 0, 0, 0);
             if (q + P + i < total_q) issue(i);
         }
         cs += P;
@@ -158,9 +218,9 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
             // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
             // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
             const int par = (ctile - t0) & 1;
-            red[par][wave][0][lane] = accg;
-            red[par][wave][1][lane] = accu;
-            __syncthreads();
+            red[par][wave][0][lane] = fold_halves(g1, g2);
+            red[par][wave][1][lane] = fold_halves(u1, u2);
+            lds_barrier();
             if (tid < 256) {
                 const int p = tid & 63, r = tid >> 6;
                 const int d = ctile / tiles_per_expert;
@@ -176,8 +236,7 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
                     act[(size_t)g.assign[d][c] * F + f0 + 4 * (p >> 4) + r] = to_bf16(swiglu(gs, us));
                 }
             }
-            accg = f32x4{0.f, 0.f, 0.f, 0.f};
-            accu = f32x4{0.f, 0.f, 0.f, 0.f};
+            g1 = g2 = u1 = u2 = zero;
             cs = 0;
             ++ctile;
         }
@@ -195,11 +254,12 @@ __global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict
     __shared__ float yacc[kMaxTok][16];
     build_groups(g, idx, T * k, E);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int col = lane & 15, kq = lane >> 4;
+    const int col = lane & 15;
+    const LaneMap lm(lane);
     const int h0 = blockIdx.x * 16;
     if (tid < kMaxTok * 16) yacc[tid >> 4][tid & 15] = 0.f;
 
-    const int k_steps = F / 32;
+    const int k_steps = F / 64;
     const int per = (k_steps + kWaves - 1) / kWaves;
     const int s_begin = wave * per;
     const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
@@ -207,21 +267,25 @@ __global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict
     const int D = g.n_active;
     const long total_q = (long)D * spt;
 
-    bf16x8 fw[P], fa[P];
+    u32x4 lo[P], hi[P], aa[P], ab[P];
     int is = 0, id = 0;
-    size_t wbase = 0, abase = 0;
+    size_t wlo = 0, whi = 0, abase = 0;
     bool acol = false;
     auto enter_expert = [&]() {
-        const size_t koff = (size_t)s_begin * 32 + kq * 8;
-        wbase = ((size_t)g.expert[id] * H + h0 + col) * F + koff;
+        const size_t row0 = (size_t)g.expert[id] * H + h0;
+        const size_t k0 = (size_t)s_begin * 64;
+        wlo = (row0 + lm.row_lo) * F + k0 + lm.k_lo;
+        whi = (row0 + lm.row_hi) * F + k0 + lm.k_hi;
         acol = col < g.cnt[id];
-        abase = (size_t)(acol ? g.assign[id][col] : 0) * F + koff;
+        abase = (size_t)(acol ? g.assign[id][col] : 0) * F + k0 + lm.kq8;
     };
     if (D > 0) enter_expert();
     auto issue = [&](int i) {
         const bool on = is < n_valid;
-        fw[i] = load_frag(w2 + wbase + is * 32, on);
-        fa[i] = load_frag(act + abase + is * 32, on && acol);
+        lo[i] = load16(w2 + wlo + is * 64, on);
+        hi[i] = load16(w2 + whi + is * 64, on);
+        aa[i] = load16(act + abase + is * 64, on && acol);
+        ab[i] = load16(act + abase + is * 64 + 32, on && acol);
         if (++is == spt) {
             is = 0;
             if (++id < D) enter_expert();
@@ -231,19 +295,23 @@ __global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict
 #pragma unroll
         for (int i = 0; i < P; ++i) issue(i);
     }
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc1 = zero, acc2 = zero;
     int cs = 0, cd = 0;
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[i], fa[i], acc, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, hi[i], lo[i]),
+                                                           __builtin_bit_cast(bf16x8, aa[i]), acc1, 0, 0, 0);
+            acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo[i], hi[i]),
+                                                           __builtin_bit_cast(bf16x8, ab[i]), acc2, 0, 0, 0);
             if (q + P + i < total_q) issue(i);
         }
         cs += P;
         if (cs == spt) {
             const int par = cd & 1;
-            red[par][wave][lane] = acc;
-            __syncthreads();
+            red[par][wave][lane] = fold_halves(acc1, acc2);
+            lds_barrier();
             if (tid < 256) {
                 const int p = tid & 63, r = tid >> 6;
                 const int c = p & 15;
@@ -255,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict
                     yacc[a / k][4 * (p >> 4) + r] += topk_w[a] * s;
                 }
             }
-            acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            acc1 = acc2 = zero;
             cs = 0;
             ++cd;
         }

@@ -358,7 +358,12 @@ struct Gemm {
                         for (int c = 0; c < 4; ++c) v[c] = acc[j][i][q * 4 + c];
                         *reinterpret_cast<f32x4*>(mine + ((size_t)((j * kTF + i) * 4 + q) * kThreads + tid) * 4) = v;
                     }
-            __threadfence();  // the piece is visible device-wide before the arrival is counted
+            // The barrier waits until every wavefront's stores have reached this XCD's L2.  One
+            // wavefront then counts the arrival with a device-scope acquire-release atomic: its
+            // release writes the whole L2's dirty lines back before the count becomes visible and
+            // its acquire drops stale lines before the pieces are read.  (Cache maintenance is per
+            // cache, not per wavefront, and costs tens of microseconds when all wavefronts of the
+            // grid issue it, so exactly one wavefront per workgroup does.)
             __syncthreads();
             int* flag = reinterpret_cast<int*>(lds);
             if (tid == 0) *flag = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
@@ -366,7 +371,6 @@ struct Gemm {
             const bool is_last = *flag == parts - 1;
             __syncthreads();  // everyone has read the flag before LDS is reused
             if (!is_last) return;  // only ever in the last round, so nothing follows for this workgroup
-            __threadfence();  // the other pieces are visible before they are read
 #pragma unroll
             for (int j = 0; j < kWF; ++j)
 #pragma unroll

@@ -72,12 +72,13 @@ __device__ inline void gate_partial(const scalar_t* __restrict__ xrow, const sca
 
 // Softmax over the E logits in acc, k passes of arg-max, renormalised weights.
 // Every lane computes the same values; lane 0 writes them and bumps the LDS histogram.
+// `bias` is the gate's bias vector (global memory or a copy in LDS) or null.
 template <int EPAD>
-__device__ inline void select_topk(float (&acc)[EPAD], const GateArgs& g, int E, int k, int t, int lane,
-                                   int* lds_hist) {
+__device__ inline void select_topk(float (&acc)[EPAD], const GateArgs& g, const float* bias, int E, int k, int t,
+                                   int lane, int* lds_hist) {
 #pragma unroll
     for (int r = 0; r < EPAD; ++r)
-        if (g.bias != nullptr && r < E) acc[r] += g.bias[r];
+        if (bias != nullptr && r < E) acc[r] += bias[r];
     float zmax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < EPAD; ++r)
@@ -137,14 +138,25 @@ __device__ inline void select_topk(float (&acc)[EPAD], const GateArgs& g, int E,
 // LDS in slice order), so a workgroup covers 16 / WPT tokens.
 //   SMALL = false: WPT = 1, grid = ceil(T / 16); per-workgroup histograms go to gate.hist.
 //   SMALL = true : one workgroup holds the whole call (T <= 16 / WPT); counts are written directly.
+//                  The call is a chain of memory latencies, so the bias vectors and the old counts
+//                  are requested before the gate rows and parked in LDS while those arrive.
 template <typename scalar_t, int EPAD, int WPT, bool SMALL>
 __global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
+    constexpr bool kViaLds = WPT > 1 || SMALL;
     __shared__ int hist[2][64];
-    __shared__ float part[(WPT > 1) ? 16 : 1][2][EPAD];
+    __shared__ float part[kViaLds ? 16 : 1][2][EPAD];
+    __shared__ float sbias[2][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int H = p.hidden, E = p.n_experts;
+    float my_bias = 0.f;
+    int old_count = 0;
+    if (SMALL) {
+        if (tid < 128 && (tid >> 6) < p.n_gates && (tid & 63) < E && p.gate[tid >> 6].bias != nullptr)
+            my_bias = p.gate[tid >> 6].bias[tid & 63];
+        if (tid < E && p.accumulate && p.counts != nullptr) old_count = p.counts[tid];
+    }
     if (tid < 128) hist[tid >> 6][tid & 63] = 0;
     __syncthreads();
-    const int H = p.hidden, E = p.n_experts;
     const int t = blockIdx.x * (16 / WPT) + wave / WPT;
     const int slice = wave % WPT;
     const bool live = t < p.tokens;
@@ -153,15 +165,16 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
     for (int g = 0; g < p.n_gates; ++g) {
         if (live) {
             gate_partial<scalar_t, EPAD>(xrow, static_cast<const scalar_t*>(p.gate[g].w), H, E, slice, WPT, lane, acc);
-            if (WPT == 1) {
-                select_topk<EPAD>(acc, p.gate[g], E, p.top_k, t, lane, hist[g]);
+            if (!kViaLds) {
+                select_topk<EPAD>(acc, p.gate[g], p.gate[g].bias, E, p.top_k, t, lane, hist[g]);
             } else if (lane == 0) {
 #pragma unroll
                 for (int r = 0; r < EPAD; ++r) part[wave][g][r] = acc[r];
             }
         }
     }
-    if (WPT > 1) {
+    if (kViaLds) {
+        if (SMALL && tid < 128) sbias[tid >> 6][tid & 63] = my_bias;
         __syncthreads();
         if (live && slice == 0) {
             for (int g = 0; g < p.n_gates; ++g) {
@@ -172,14 +185,16 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
                     for (int w = 0; w < WPT; ++w) s += part[wave + w][g][r];
                     acc[r] = s;
                 }
-                select_topk<EPAD>(acc, p.gate[g], E, p.top_k, t, lane, hist[g]);
+                const float* bias = p.gate[g].bias;
+                if (SMALL && bias != nullptr) bias = sbias[g];
+                select_topk<EPAD>(acc, p.gate[g], bias, E, p.top_k, t, lane, hist[g]);
             }
         }
     }
     __syncthreads();
     if (tid < E) {
         if (SMALL) {
-            if (p.counts != nullptr) p.counts[tid] = (p.accumulate ? p.counts[tid] : 0) + hist[0][tid];
+            if (p.counts != nullptr) p.counts[tid] = old_count + hist[0][tid];
             if (p.counts_next != nullptr) p.counts_next[tid] = hist[1][tid];
         } else {
             for (int g = 0; g < p.n_gates; ++g)
