@@ -151,15 +151,16 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
  * recorded on the caller's stream between the kernels of each entry-point
  * call made by THIS thread between begin and end.  Stages: 0 routing (gate,
  * softmax, top-k, prediction), 1 counts + permutation, 2 grouped GEMM1 +
- * SwiGLU, 3 grouped GEMM2 (the decode path folds the combine into it),
- * 4 combine.  begin allocates events for up to max_calls calls (later calls
+ * SwiGLU, 3 grouped GEMM2, 4 combine, 5 the single kernel that runs a bf16
+ * call of at most 16 tokens (routing when the entry point routes, both
+ * GEMMs, combine).  begin allocates events for up to max_calls calls (later calls
  * are not recorded); end synchronises with the last recorded event, writes
  * the mean milliseconds per launch of each stage and the number of launches
  * averaged (either pointer may be NULL), and frees the events.
  * Errors: MOE_ERR_SHAPE (bad max_calls, begin twice, end without begin),
  * MOE_ERR_DEVICE.
  */
-#define MOE_NUM_STAGES 5
+#define MOE_NUM_STAGES 6
 int moe_stage_timing_begin(int32_t max_calls);
 int moe_stage_timing_end(float* stage_ms, int32_t* stage_launches);
 

@@ -1,11 +1,18 @@
-// Expert FFN for decode-size calls (a handful of tokens), bf16 storage.
+// The MoE layer for decode-size calls (a handful of tokens), bf16 storage, as
+// ONE persistent kernel: routing, both expert GEMMs and the weighted combine.
 //
 // With the experts resident in HBM, a decode step of the MoE layer is a weight
 // stream: each selected expert's three matrices are read once and multiplied
 // by a few hidden states (the paper's Table I discussion: expert parameters
-// dwarf the activations by four orders of magnitude).  These two kernels are
-// therefore organised around the HBM stream, not around the arithmetic:
+// dwarf the activations by four orders of magnitude).  At one token the stream
+// lasts little more than 100 microseconds, so every kernel boundary, cold
+// start and dependent memory latency is a visible fraction of the layer.  The
+// kernel is therefore organised around the HBM stream, not around the
+// arithmetic:
 //
+//   * every workgroup evaluates the gate for all tokens itself (the gate is
+//     64-128 KB and the arithmetic is the same everywhere, so all workgroups
+//     agree bit for bit); workgroup 0 publishes indices, weights and counts;
 //   * no permutation and no LDS staging of weights: every weight byte is used
 //     by exactly one wavefront, so it is loaded straight into MFMA operand
 //     registers with 16-byte loads;
@@ -29,22 +36,37 @@
 //     stream never drains;
 //   * the 8 wavefronts of a workgroup split K, and their partial 16 x 16 tiles
 //     are summed through LDS in a fixed order (deterministic);
-//   * the token groups are rebuilt by every workgroup from topk_idx (at most
-//     128 integers), which is cheaper than another kernel launch.
+//   * between the two GEMMs every workgroup needs the whole intermediate
+//     vector: a grid-wide barrier made of one arrival flag per workgroup, each
+//     set to a per-launch epoch, so the flags never need clearing and no
+//     read-modify-write atomic is contended.  The intermediate is written with
+//     device-scope (write-through) stores, so it has reached memory when the
+//     flag is raised, and it is read with ordinary loads only after the
+//     barrier: no L2 holds an older copy, because caches are invalidated when
+//     a kernel starts and nothing reads the intermediate before the barrier.
+//     This keeps the barrier free of cache write-backs and invalidations (a
+//     device-scope fence issued by every wavefront of the grid costs tens of
+//     microseconds here).  The first P steps of the second GEMM's weights are
+//     requested before the barrier is awaited, so the stream continues across
+//     it.
 //
-//   dec_gemm1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f])   a = t*k + j, e = idx[a]
-//   dec_gemm2: y[t, h]   = sum over the token's experts (ascending expert id) of
-//                          w[a] * (act[a] . w2[e, h]),  fp32, one rounding to bf16
+//   phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f])   a = t*k + j, e = idx[a]
+//   phase 2: y[t, h]   = sum over the token's experts (ascending expert id) of
+//                        w[a] * (act[a] . w2[e, h]),  fp32, one rounding to bf16
+#include <atomic>
+
 #include "bf16_utils.h"
 #include "moe_internal.h"
+#include "route_device.h"
 
 namespace moe {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-// Pipeline depths (k32 steps of loads in flight per wavefront) of the two kernels.
+// Pipeline depths (64-element K steps of loads in flight per wavefront) of the two GEMM phases.
 #ifndef MOE_DEC_P1
 #define MOE_DEC_P1 4
 #endif
@@ -56,16 +78,38 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kMaxTok = kDecodeMaxTokens;
 static_assert(kMaxTok == 16, "an expert's tokens are the 16 columns of one 16x16x32 MFMA");
+static_assert(kThreads == kSmallRouteThreads && kMaxTok == kSmallRouteMaxTokens, "routing runs in the same workgroup");
+
+struct DecodeArgs {
+    const uint16_t* x;      // [T, H]
+    // routing: either a gate to evaluate (wg != null; idx_out / w_out / counts are written by
+    // workgroup 0) or selections made earlier (idx_in / w_in)
+    const uint16_t* wg;
+    const float* bias;
+    int32_t* idx_out;
+    float* w_out;
+    int32_t* counts;
+    int accumulate;
+    const int32_t* idx_in;
+    const float* w_in;
+    const uint16_t *w1, *w3, *w2;
+    uint16_t* act;          // [T*k, F] workspace
+    uint16_t* y;            // [T, H]
+    uint32_t* flags;        // [gridDim.x] workspace: arrival flags of the grid-wide barrier
+    uint32_t epoch;         // value that marks an arrival in this launch
+    int T, k, E, H, F;
+};
 
 struct Groups {
     int n_active;
-    int expert[64];         // active experts, ascending id
-    int cnt[64];            // tokens of that expert (<= 16)
+    int expert[64];           // active experts, ascending id
+    int cnt[64];              // tokens of that expert (<= 16)
     int assign[64][kMaxTok];  // their assignment ids t*k + j, ascending
 };
 
-// Builds the per-expert token lists; call with all threads, ends with a barrier.
-__device__ void build_groups(Groups& g, const int32_t* __restrict__ idx, int A, int E) {
+// Builds the per-expert token lists from the selections in LDS; call with all threads, ends with
+// a barrier.
+__device__ void build_groups(Groups& g, const int* idx, int A, int E) {
     const int tid = threadIdx.x;
     if (tid < 64) {
         int c = 0;
@@ -90,8 +134,6 @@ __device__ void build_groups(Groups& g, const int32_t* __restrict__ idx, int A, 
     }
     __syncthreads();
 }
-
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 __device__ inline u32x4 load16(const uint16_t* p, bool on) {
     u32x4 v = {0u, 0u, 0u, 0u};
@@ -139,18 +181,22 @@ struct LaneMap {
     }
 };
 
+struct Smem {
+    RouteSmem route;
+    Groups g;
+    f32x4 red[2][kWaves][2][64];
+    float yacc[kMaxTok][16];
+};
+
+// ---- phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f]) over this workgroup's share
+// of the (active expert, 16-feature tile) list.
 template <int P>
-__global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict__ x,
-                                                       const int32_t* __restrict__ idx,
-                                                       const uint16_t* __restrict__ w1,
-                                                       const uint16_t* __restrict__ w3, int T, int k, int E, int H,
-                                                       int F, uint16_t* __restrict__ act) {
-    __shared__ Groups g;
-    __shared__ f32x4 red[2][kWaves][2][64];
-    build_groups(g, idx, T * k, E);
+__device__ inline void gemm1_phase(const DecodeArgs& p, Smem& sm) {
+    const Groups& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
     const LaneMap lm(lane);
+    const int H = p.H, F = p.F, k = p.k;
 
     const int tiles_per_expert = F / 16;
     const int total_tiles = g.n_active * tiles_per_expert;
@@ -185,12 +231,12 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
     enter_tile();
     auto issue = [&](int i) {
         const bool on = is < n_valid;
-        lo1[i] = load16(w1 + wlo + is * 64, on);
-        hi1[i] = load16(w1 + whi + is * 64, on);
-        lo3[i] = load16(w3 + wlo + is * 64, on);
-        hi3[i] = load16(w3 + whi + is * 64, on);
-        xa[i] = load16(x + xbase + is * 64, on && xcol);
-        xb[i] = load16(x + xbase + is * 64 + 32, on && xcol);
+        lo1[i] = load16(p.w1 + wlo + is * 64, on);
+        hi1[i] = load16(p.w1 + whi + is * 64, on);
+        lo3[i] = load16(p.w3 + wlo + is * 64, on);
+        hi3[i] = load16(p.w3 + whi + is * 64, on);
+        xa[i] = load16(p.x + xbase + is * 64, on && xcol);
+        xb[i] = load16(p.x + xbase + is * 64 + 32, on && xcol);
         if (++is == spt) {
             is = 0;
             if (++itile < t1) enter_tile();
@@ -218,22 +264,30 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
             // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
             // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
             const int par = (ctile - t0) & 1;
-            red[par][wave][0][lane] = fold_halves(g1, g2);
-            red[par][wave][1][lane] = fold_halves(u1, u2);
+            sm.red[par][wave][0][lane] = fold_halves(g1, g2);
+            sm.red[par][wave][1][lane] = fold_halves(u1, u2);
             lds_barrier();
-            if (tid < 256) {
-                const int p = tid & 63, r = tid >> 6;
+            if (tid < 128) {
+                const int pl = tid & 63, rp = tid >> 6;  // features 2 * rp and 2 * rp + 1 of the lane's four
                 const int d = ctile / tiles_per_expert;
                 const int f0 = (ctile - d * tiles_per_expert) * 16;
-                const int c = p & 15;
+                const int c = pl & 15;
                 if (c < g.cnt[d]) {
-                    float gs = 0.f, us = 0.f;
+                    float o[2];
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) {
-                        gs += red[par][w][0][p][r];
-                        us += red[par][w][1][p][r];
+                    for (int h = 0; h < 2; ++h) {
+                        float gs = 0.f, us = 0.f;
+#pragma unroll
+                        for (int w = 0; w < kWaves; ++w) {
+                            gs += sm.red[par][w][0][pl][2 * rp + h];
+                            us += sm.red[par][w][1][pl][2 * rp + h];
+                        }
+                        o[h] = swiglu(gs, us);
                     }
-                    act[(size_t)g.assign[d][c] * F + f0 + 4 * (p >> 4) + r] = to_bf16(swiglu(gs, us));
+                    // device-scope (write-through) store: read by other workgroups after the grid barrier
+                    uint32_t* dst = reinterpret_cast<uint32_t*>(p.act + (size_t)g.assign[d][c] * F + f0 +
+                                                                4 * (pl >> 4) + 2 * rp);
+                    __hip_atomic_store(dst, pack_bf16x2(o[0], o[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
             g1 = g2 = u1 = u2 = zero;
@@ -243,61 +297,98 @@ __global__ __launch_bounds__(kThreads) void dec_gemm1(const uint16_t* __restrict
     }
 }
 
+// ---- phase 2: y[t, h] = sum over the token's experts (ascending expert id) of
+// w[a] * (act[a] . w2[e, h]) for this workgroup's 16-row tiles of h.  The first P steps of weight
+// loads are issued before the grid-wide barrier that `act` has to wait for.
 template <int P>
-__global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict__ act,
-                                                       const int32_t* __restrict__ idx,
-                                                       const float* __restrict__ topk_w,
-                                                       const uint16_t* __restrict__ w2, int T, int k, int E, int H,
-                                                       int F, uint16_t* __restrict__ y) {
-    __shared__ Groups g;
-    __shared__ f32x4 red[2][kWaves][64];
-    __shared__ float yacc[kMaxTok][16];
-    build_groups(g, idx, T * k, E);
+__device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
+    const Groups& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
     const LaneMap lm(lane);
-    const int h0 = blockIdx.x * 16;
-    if (tid < kMaxTok * 16) yacc[tid >> 4][tid & 15] = 0.f;
+    const int H = p.H, F = p.F, k = p.k;
+    const int n_wgs = gridDim.x;
 
+    const int h_tiles = H / 16;
+    const int my_tiles = blockIdx.x < h_tiles ? (h_tiles - 1 - blockIdx.x) / n_wgs + 1 : 0;
     const int k_steps = F / 64;
     const int per = (k_steps + kWaves - 1) / kWaves;
     const int s_begin = wave * per;
     const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
     const int spt = (per + P - 1) / P * P;
     const int D = g.n_active;
-    const long total_q = (long)D * spt;
+    const long total_q = (long)my_tiles * D * spt;
+    const size_t k0 = (size_t)s_begin * 64;
+
+    // ---- everything this workgroup stored to `act` has left the CU; announce it
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) __hip_atomic_store(&p.flags[blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (total_q == 0) return;
 
     u32x4 lo[P], hi[P], aa[P], ab[P];
-    int is = 0, id = 0;
-    size_t wlo = 0, whi = 0, abase = 0;
-    bool acol = false;
-    auto enter_expert = [&]() {
-        const size_t row0 = (size_t)g.expert[id] * H + h0;
-        const size_t k0 = (size_t)s_begin * 64;
+    // weight-side issue state
+    int ws = 0, wd = 0, wt = blockIdx.x;
+    size_t wlo = 0, whi = 0;
+    auto enter_w = [&]() {
+        const size_t row0 = (size_t)g.expert[wd] * H + wt * 16;
         wlo = (row0 + lm.row_lo) * F + k0 + lm.k_lo;
         whi = (row0 + lm.row_hi) * F + k0 + lm.k_hi;
-        acol = col < g.cnt[id];
-        abase = (size_t)(acol ? g.assign[id][col] : 0) * F + k0 + lm.kq8;
     };
-    if (D > 0) enter_expert();
-    auto issue = [&](int i) {
-        const bool on = is < n_valid;
-        lo[i] = load16(w2 + wlo + is * 64, on);
-        hi[i] = load16(w2 + whi + is * 64, on);
-        aa[i] = load16(act + abase + is * 64, on && acol);
-        ab[i] = load16(act + abase + is * 64 + 32, on && acol);
-        if (++is == spt) {
-            is = 0;
-            if (++id < D) enter_expert();
+    enter_w();
+    auto issue_w = [&](int i) {
+        const bool on = ws < n_valid;
+        lo[i] = load16(p.w2 + wlo + ws * 64, on);
+        hi[i] = load16(p.w2 + whi + ws * 64, on);
+        if (++ws == spt) {
+            ws = 0;
+            if (++wd == D) {
+                wd = 0;
+                wt += n_wgs;
+            }
+            if (wt < h_tiles) enter_w();
         }
     };
-    if (D > 0) {
+    // act-side issue state (the operand does not depend on the h tile)
+    int as = 0, ad = 0;
+    size_t abase = 0;
+    bool acol = false;
+    auto enter_a = [&]() {
+        acol = col < g.cnt[ad];
+        abase = (size_t)(acol ? g.assign[ad][col] : 0) * F + k0 + lm.kq8;
+    };
+    enter_a();
+    auto issue_a = [&](int i) {
+        const bool on = as < n_valid && acol;
+        aa[i] = load16(p.act + abase + as * 64, on);
+        ab[i] = load16(p.act + abase + as * 64 + 32, on);
+        if (++as == spt) {
+            as = 0;
+            if (++ad == D) ad = 0;
+            enter_a();
+        }
+    };
 #pragma unroll
-        for (int i = 0; i < P; ++i) issue(i);
+    for (int i = 0; i < P; ++i) issue_w(i);
+
+    // ---- grid-wide barrier: wait until every workgroup's flag carries this launch's epoch.
+    // The spin is bounded, so the kernel ends even if workgroups never become co-resident.
+    if (tid < 64) {
+        for (int it = 0; it < (1 << 22); ++it) {
+            bool all = true;
+            for (int i = tid; i < n_wgs; i += 64)
+                all &= __hip_atomic_load(&p.flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.epoch;
+            if (__all(all)) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
     }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < P; ++i) issue_a(i);
+
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     f32x4 acc1 = zero, acc2 = zero;
-    int cs = 0, cd = 0;
+    int cs = 0, cd = 0, ct = blockIdx.x, par = 0;
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
@@ -305,52 +396,122 @@ __global__ __launch_bounds__(kThreads) void dec_gemm2(const uint16_t* __restrict
                                                            __builtin_bit_cast(bf16x8, aa[i]), acc1, 0, 0, 0);
             acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo[i], hi[i]),
                                                            __builtin_bit_cast(bf16x8, ab[i]), acc2, 0, 0, 0);
-            if (q + P + i < total_q) issue(i);
+            if (q + P + i < total_q) {
+                issue_w(i);
+                issue_a(i);
+            }
         }
         cs += P;
         if (cs == spt) {
-            const int par = cd & 1;
-            red[par][wave][lane] = fold_halves(acc1, acc2);
+            sm.red[par][wave][0][lane] = fold_halves(acc1, acc2);
             lds_barrier();
             if (tid < 256) {
-                const int p = tid & 63, r = tid >> 6;
-                const int c = p & 15;
+                const int pl = tid & 63, r = tid >> 6;
+                const int c = pl & 15;
                 if (c < g.cnt[cd]) {
                     float s = 0.f;
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) s += red[par][w][p][r];
+                    for (int w = 0; w < kWaves; ++w) s += sm.red[par][w][0][pl][r];
                     const int a = g.assign[cd][c];
-                    yacc[a / k][4 * (p >> 4) + r] += topk_w[a] * s;
+                    sm.yacc[a / k][4 * (pl >> 4) + r] += sm.route.w[a] * s;
                 }
             }
             acc1 = acc2 = zero;
             cs = 0;
-            ++cd;
+            par ^= 1;
+            if (++cd == D) {
+                lds_barrier();  // the tile's sums are complete
+                if (tid < p.T * 16) {
+                    const int t = tid >> 4, r = tid & 15;
+                    p.y[(size_t)t * H + ct * 16 + r] = to_bf16(sm.yacc[t][r]);
+                    sm.yacc[t][r] = 0.f;
+                }
+                cd = 0;
+                ct += n_wgs;
+            }
         }
-    }
-    __syncthreads();
-    if (tid < T * 16) {
-        const int t = tid >> 4, r = tid & 15;
-        y[(size_t)t * H + h0 + r] = to_bf16(yacc[t][r]);
     }
 }
 
+// The whole MoE layer of a decode-size call in one launch.  Every workgroup must be resident at
+// the same time (grid <= number of compute units, one 512-thread workgroup each).
+template <int P1, int P2, bool ROUTE>
+__global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
+    __shared__ Smem sm;
+    const int tid = threadIdx.x;
+    const int A = p.T * p.k;
+    if (tid < kMaxTok * 16) sm.yacc[tid >> 4][tid & 15] = 0.f;
+    if (ROUTE) {
+        // Every workgroup routes the call itself (identical arithmetic, identical result), which
+        // costs a few microseconds of latency instead of a kernel boundary; workgroup 0 publishes.
+        int old_count = 0;
+        const bool publish = blockIdx.x == 0;
+        if (publish && tid < p.E && p.accumulate) old_count = p.counts[tid];
+        static_assert(sizeof(sm.red) >= kRoutePartFloats * sizeof(float), "routing borrows the reduction buffer");
+        route_tokens_wg<uint16_t>(p.x, p.wg, p.bias, p.T, p.H, p.E, p.k, sm.route,
+                                  reinterpret_cast<float*>(&sm.red[0][0][0][0]));
+        if (publish) {
+            if (tid < A) {
+                p.idx_out[tid] = sm.route.idx[tid];
+                p.w_out[tid] = sm.route.w[tid];
+            }
+            if (tid < p.E) {
+                int c = 0;
+                for (int a = 0; a < A; ++a) c += sm.route.idx[a] == tid;
+                p.counts[tid] = old_count + c;
+            }
+        }
+    } else {
+        if (tid < A) {
+            sm.route.idx[tid] = p.idx_in[tid];
+            sm.route.w[tid] = p.w_in[tid];
+        }
+        __syncthreads();
+    }
+    build_groups(sm.g, sm.route.idx, A, p.E);
+    gemm1_phase<P1>(p, sm);
+    gemm2_phase<P2>(p, sm);
+}
+
+std::atomic<uint32_t> g_epoch{0};
+
 }  // namespace
 
-hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* x, const int32_t* topk_idx,
-                                  const float* topk_w, const void* w1, const void* w3, const void* w2, void* y,
-                                  void* act, hipStream_t stream) {
-    const int max_tiles = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
-    const int grid1 = min(compute_units(), max_tiles);
-    dec_gemm1<MOE_DEC_P1><<<grid1, kThreads, 0, stream>>>(static_cast<const uint16_t*>(x), topk_idx,
-                                                 static_cast<const uint16_t*>(w1), static_cast<const uint16_t*>(w3),
-                                                 tokens, s.top_k, s.n_experts, s.hidden, s.ffn,
-                                                 static_cast<uint16_t*>(act));
-    stage_mark(stream, kStageGemm1);
-    dec_gemm2<MOE_DEC_P2><<<s.hidden / 16, kThreads, 0, stream>>>(static_cast<const uint16_t*>(act), topk_idx, topk_w,
-                                                          static_cast<const uint16_t*>(w2), tokens, s.top_k,
-                                                          s.n_experts, s.hidden, s.ffn, static_cast<uint16_t*>(y));
-    stage_mark(stream, kStageGemm2);
+hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
+                               const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
+                               const void* w2, void* y, void* act, uint32_t* flags, hipStream_t stream) {
+    DecodeArgs p{};
+    p.x = static_cast<const uint16_t*>(x);
+    if (route != nullptr) {
+        p.wg = static_cast<const uint16_t*>(route->w_gate);
+        p.bias = route->bias;
+        p.idx_out = route->idx;
+        p.w_out = route->wts;
+        p.counts = route->counts;
+        p.accumulate = route->accumulate;
+    } else {
+        p.idx_in = topk_idx;
+        p.w_in = topk_w;
+    }
+    p.w1 = static_cast<const uint16_t*>(w1);
+    p.w3 = static_cast<const uint16_t*>(w3);
+    p.w2 = static_cast<const uint16_t*>(w2);
+    p.act = static_cast<uint16_t*>(act);
+    p.y = static_cast<uint16_t*>(y);
+    p.flags = flags;
+    uint32_t epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
+    if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
+    p.epoch = epoch;
+    p.T = tokens;
+    p.k = s.top_k;
+    p.E = s.n_experts;
+    p.H = s.hidden;
+    p.F = s.ffn;
+    const int max_tiles1 = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
+    const int grid = min(min(compute_units(), kDecodeFlagInts), max(max_tiles1, s.hidden / 16));
+    if (route != nullptr) decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, true><<<grid, kThreads, 0, stream>>>(p);
+    else decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false><<<grid, kThreads, 0, stream>>>(p);
+    stage_mark(stream, kStageFused);
     return hipGetLastError();
 }
 

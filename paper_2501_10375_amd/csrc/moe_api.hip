@@ -18,6 +18,7 @@ WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
     L.row_of_slot = off; off = align_up(off + A * sizeof(int32_t));
     L.slot_of = off;     off = align_up(off + A * sizeof(int32_t));
     L.sync = off;        off = align_up(off + kSyncInts * sizeof(int32_t));
+    L.dec_flags = off;   off = align_up(off + kDecodeFlagInts * sizeof(uint32_t));
     L.route_end = off;
     L.act = off;         off = align_up(off + A * (size_t)s.ffn * esz);
     L.out = off;         off = align_up(off + A * (size_t)s.hidden * sizeof(float));
@@ -114,6 +115,7 @@ bool decode_path(const moe_shape_t& s, int tokens) { return s.dtype == MOE_BF16 
 
 struct Ws {
     int32_t *hist, *hist_next, *offs, *row_of_slot, *slot_of, *sync;
+    uint32_t* dec_flags;
     void* act;
     float* out;
     float* partial;
@@ -128,6 +130,7 @@ Ws carve(void* workspace, const WorkspaceLayout& L) {
     w.row_of_slot = reinterpret_cast<int32_t*>(b + L.row_of_slot);
     w.slot_of = reinterpret_cast<int32_t*>(b + L.slot_of);
     w.sync = reinterpret_cast<int32_t*>(b + L.sync);
+    w.dec_flags = reinterpret_cast<uint32_t*>(b + L.dec_flags);
     w.act = b + L.act;
     w.out = reinterpret_cast<float*>(b + L.out);
     w.partial = reinterpret_cast<float*>(b + L.partial);
@@ -166,7 +169,8 @@ hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* 
 
 hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_t* idx, const float* w,
                    const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream) {
-    if (decode_path(s, tokens)) return launch_ffn_bf16_decode(s, tokens, x, idx, w, w1, w3, w2, y, ws.act, stream);
+    if (decode_path(s, tokens))
+        return launch_decode_layer(s, tokens, x, nullptr, idx, w, w1, w3, w2, y, ws.act, ws.dec_flags, stream);
     if (s.dtype == MOE_F32)
         return launch_ffn_f32(s, tokens, static_cast<const float*>(x), w, static_cast<const float*>(w1),
                               static_cast<const float*>(w3), static_cast<const float*>(w2), static_cast<float*>(y),
@@ -302,6 +306,18 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
     if (tokens == 0)
         return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, nullptr, stream));
     stage_call_begin(stream);
+    if (decode_path(*shape, tokens)) {
+        // One kernel routes and runs the experts; the prediction gate, which nothing downstream in
+        // this call waits for, follows in a small launch of its own.
+        const DecodeRoute r = {w_gate, gate_bias, topk_idx, topk_w, counts, accumulate};
+        hipError_t e = launch_decode_layer(*shape, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags,
+                                           stream);
+        if (e != hipSuccess || w_gate_next == nullptr) return dev(e);
+        GateArgs gn[1] = {{w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
+        e = launch_route_small(*shape, tokens, x, gn, 1, nullptr, 0, nullptr, stream);
+        stage_mark(stream, kStageRoute);
+        return dev(e);
+    }
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;
     hipError_t e = run_route(*shape, tokens, x, g, n_gates, counts, accumulate, nullptr, !decode_path(*shape, tokens), ws,

@@ -12,9 +12,9 @@ namespace moe {
 
 // Tokens handled by one workgroup of the routing / histogram / permute kernels.
 constexpr int kRouteTokensPerBlock = 16;
-// Calls with at most this many tokens take the decode path: one fused routing
-// kernel and two weight-streaming kernels that group tokens per expert on the
-// fly, without a permutation in the workspace.
+// Calls with at most this many tokens take the decode path: one persistent
+// weight-streaming kernel that routes, groups tokens per expert on the fly
+// (no permutation in the workspace) and runs both expert GEMMs.
 constexpr int kDecodeMaxTokens = 16;
 
 // Rows (tokens) per M-tile of the grouped GEMMs; an M-tile never spans two experts.
@@ -28,6 +28,7 @@ struct WorkspaceLayout {
     size_t row_of_slot;  // int32 [A]            slot -> assignment index t*k + j
     size_t slot_of;      // int32 [A]            assignment index -> slot
     size_t sync;         // int32 [kSyncInts]    rendezvous / arrival counters of the two grouped GEMMs
+    size_t dec_flags;    // uint32 [kDecodeFlagInts]  arrival flags of the decode kernel's grid barrier
     size_t route_end;    // bytes needed by routing-only calls
     size_t act;          // dtype [A, F]         silu(W1 x) * (W3 x)
     size_t out;          // fp32  [A, H]         per-assignment expert output
@@ -51,7 +52,11 @@ struct GateArgs {
 };
 
 // Stage ids of the optional per-stage timing (moe_stage_timing_begin/end in moe.h).
-enum Stage { kStageRoute = 0, kStagePermute = 1, kStageGemm1 = 2, kStageGemm2 = 3, kStageCombine = 4 };
+enum Stage {
+    kStageRoute = 0, kStagePermute = 1, kStageGemm1 = 2, kStageGemm2 = 3, kStageCombine = 4,
+    kStageFused = 5,  // the single kernel of a decode-size bf16 call
+};
+static_assert(kStageFused + 1 == MOE_NUM_STAGES, "moe.h lists the stages");
 // Records "stage `stage` ends here" on `stream`; a no-op unless timing is active on this thread.
 void stage_mark(hipStream_t stream, int stage);
 
@@ -100,10 +105,21 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
 // Number of compute units of the current device (cached per device).
 int compute_units();
 
-// Weight-streaming expert FFN, bf16 storage (tokens <= kDecodeMaxTokens).
-hipError_t launch_ffn_bf16_decode(const moe_shape_t& s, int tokens, const void* x,
-                                  const int32_t* topk_idx, const float* topk_w, const void* w1,
-                                  const void* w3, const void* w2, void* y, void* act,
-                                  hipStream_t stream);
+// Decode-size bf16 calls (tokens <= kDecodeMaxTokens): one persistent kernel streams the selected
+// experts' weights.  With `route` it first evaluates the gate (and writes indices, weights and
+// counts); without, it takes topk_idx / topk_w.  `flags` are kDecodeFlagInts words of workspace
+// whose contents need not be initialised.
+constexpr int kDecodeFlagInts = 512;
+struct DecodeRoute {
+    const void* w_gate;
+    const float* bias;
+    int32_t* idx;
+    float* wts;
+    int32_t* counts;
+    int accumulate;
+};
+hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
+                               const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
+                               const void* w2, void* y, void* act, uint32_t* flags, hipStream_t stream);
 
 }  // namespace moe

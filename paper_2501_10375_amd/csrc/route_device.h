@@ -1,0 +1,176 @@
+// Device code of the gating function shared by the routing kernels and the
+// fused decode kernel (DAOP paper Sec. II-A "MoE Structure": gate logits,
+// softmax over all experts, top-k with renormalised weights; the same
+// computation with the next layer's gate gives the prediction of Sec. III
+// observation 3 / Sec. IV-C).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe {
+
+__device__ inline void load8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+__device__ inline void load8(const uint16_t* p, float (&v)[8]) {
+    const uint4 q = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ---- routing of a decode-size call (at most 16 tokens) by one workgroup of 8 wavefronts ----
+
+constexpr int kSmallRouteThreads = 512;
+constexpr int kSmallRouteMaxTokens = 16;
+
+struct RouteSmem {
+    int idx[kSmallRouteMaxTokens * 8];
+    float w[kSmallRouteMaxTokens * 8];
+};
+// Floats of LDS scratch route_tokens_wg needs: [wavefront][token][expert] partial logits.
+constexpr int kRoutePartFloats = 8 * kSmallRouteMaxTokens * 64;
+
+// Sums acc[0..8) over the 64 lanes with a halving exchange: after the three exchange steps each
+// lane carries one of the 8 values (which one is given by lane bits 5, 4, 3), after three more
+// butterfly steps lanes with (lane & 7) == 0 hold the full sum of value
+// 4 * bit5 + 2 * bit4 + bit3.  10 shuffles instead of 48, in a fixed order.
+__device__ inline float reduce8_scatter(const float (&acc)[8], int lane) {
+    const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
+    float v4[4], v2[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float keep = b5 ? acc[4 + i] : acc[i];
+        const float give = b5 ? acc[i] : acc[4 + i];
+        v4[i] = keep + __shfl_xor(give, 32, 64);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const float keep = b4 ? v4[2 + i] : v4[i];
+        const float give = b4 ? v4[i] : v4[2 + i];
+        v2[i] = keep + __shfl_xor(give, 16, 64);
+    }
+    const float keep = b3 ? v2[1] : v2[0];
+    const float give = b3 ? v2[0] : v2[1];
+    float v = keep + __shfl_xor(give, 8, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 1, 64);
+    return v;
+}
+
+// Routes tokens 0..T (T <= 16) against one gate; every thread of the 512-thread workgroup calls
+// it.  On return (after a workgroup barrier) sm.idx[t*k + j] / sm.w[t*k + j] hold expert and
+// renormalised weight of selection j of token t, in descending probability, ties to the lower
+// index.  The arithmetic depends only on (T, H, E, k), never on the workgroup, so any number of
+// workgroups computing the same call agree bit for bit.  `part` is kRoutePartFloats of LDS.
+//
+// The 8 wavefronts split the hidden dimension in interleaved 512-element chunks, so the gate and
+// x are read once per workgroup whatever T is; a wavefront walks the tokens two at a time over
+// its chunks (the gate pieces of later tokens come from the vector cache).  Per-wavefront partial
+// logits are summed in wavefront order through LDS; the softmax and the k arg-max passes run
+// across the lanes of one wavefront, lane e holding expert e.
+template <typename scalar_t>
+__device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const scalar_t* __restrict__ wg,
+                                       const float* __restrict__ bias, int T, int H, int E, int k, RouteSmem& sm,
+                                       float* part) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // requested first so that it arrives together with the gate rows
+    const float my_bias = (bias != nullptr && lane < E) ? bias[lane] : 0.f;
+    const int n_blocks = (E + 7) / 8;
+    const int esub = ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+    for (int t = 0; t < T; t += 2) {
+        const bool two = t + 1 < T;
+        const scalar_t* x0 = x + (size_t)t * H;
+        const scalar_t* x1 = x + (size_t)(two ? t + 1 : t) * H;
+        for (int eb = 0; eb < n_blocks; ++eb) {
+            const int ne = min(8, E - eb * 8);
+            const scalar_t* wrow = wg + (size_t)eb * 8 * H;
+            float acc0[8], acc1[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) acc0[r] = acc1[r] = 0.f;
+            for (int h = (wave * 64 + lane) * 8; h < H; h += 8 * 512) {
+                float xv0[8], xv1[8];
+                load8(x0 + h, xv0);
+                load8(x1 + h, xv1);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    if (r < ne) {
+                        float wv[8];
+                        load8(wrow + (size_t)r * H + h, wv);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            acc0[r] = fmaf(xv0[i], wv[i], acc0[r]);
+                            acc1[r] = fmaf(xv1[i], wv[i], acc1[r]);
+                        }
+                    }
+                }
+            }
+            const float v0 = reduce8_scatter(acc0, lane);
+            const float v1 = reduce8_scatter(acc1, lane);
+            if ((lane & 7) == 0) {
+                part[(wave * T + t) * 64 + eb * 8 + esub] = v0;
+                if (two) part[(wave * T + t + 1) * 64 + eb * 8 + esub] = v1;
+            }
+        }
+    }
+    __syncthreads();
+    for (int t = wave; t < T; t += 8) {
+        float z = -INFINITY;
+        if (lane < E) {
+            float s = 0.f;
+            for (int w = 0; w < 8; ++w) s += part[(w * T + t) * 64 + lane];
+            z = s + my_bias;
+        }
+        const float zmax = wave_max(z);
+        float p = lane < E ? expf(z - zmax) : 0.f;
+        p = p / wave_sum(p);
+        // k passes of arg-max across the lanes; the lowest lane among equals wins
+        bool taken = lane >= E;
+        int my_sel = 0;
+        float my_p = 0.f, wsum = 0.f;
+        for (int j = 0; j < k; ++j) {
+            const float cand = taken ? -1.f : p;
+            float best = wave_max(cand);
+            uint64_t m = __ballot(!taken && cand == best);
+            if (m == 0) {  // only with non-finite inputs: still select a valid, distinct expert
+                m = __ballot(!taken);
+                best = 0.f;
+            }
+            const int sel = __ffsll((long long)m) - 1;
+            if (lane == sel) taken = true;
+            if (lane == j) {
+                my_sel = sel;
+                my_p = best;
+            }
+            wsum += best;
+        }
+        if (lane < k) {
+            sm.idx[t * k + lane] = my_sel;
+            sm.w[t * k + lane] = my_p / wsum;
+        }
+    }
+    __syncthreads();
+}
+
+}  // namespace moe

@@ -23,7 +23,7 @@ STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTY
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
            "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_stage_timing_begin", "moe_stage_timing_end")
-STAGES = ("route", "permute", "gemm1", "gemm2", "combine")
+STAGES = ("route", "permute", "gemm1", "gemm2", "combine", "fused")
 
 
 class MoeShape(ctypes.Structure):

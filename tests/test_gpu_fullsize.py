@@ -68,3 +68,23 @@ def test_phi_prefill_and_decode(oracle, phi):
     top4 = torch.sort(res["counts"], descending=True).values[:4].sum().item() / res["counts"].sum().item()
     assert top4 > 0.8  # four experts take most tokens (load-imbalance stress)
     _layer(oracle, phi, PHI, 1, 1, "phi decode T=1")
+
+
+@pytest.mark.parametrize("T", [1, 5])
+def test_mixtral_decode_sequence_on_one_workspace(mixtral, T):
+    """Decode steps share one workspace: the intermediate of an earlier step must never be what a
+    later step reads (its caches may still hold it), and the barrier flags need no clearing."""
+    c = MIXTRAL
+    shape = moe.make_shape(c["H"], c["F"], c["E"], c["k"], torch.bfloat16)
+    shared = moe.LayerOutputs(shape, T, torch.bfloat16, DEV, predict=False)
+    for step in range(6):
+        x = synth.normal((T, c["H"]), 2000 + step, synth.TID_X, 1.0, torch.bfloat16, DEV)
+        call = dict(mixtral, x=x, wg_next=None, bias_next=None)
+        got = moe.run_layer(shape, call, shared, predict=False)
+        y, idx = got["y"].clone(), got["idx"].clone()
+        fresh = moe.LayerOutputs(shape, T, torch.bfloat16, DEV, predict=False)
+        fresh.workspace.fill_(0xA5)
+        ref = moe.run_layer(shape, call, fresh, predict=False)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, ref["idx"]), f"step {step}"
+        assert torch.equal(y.view(torch.int16), ref["y"].view(torch.int16)), f"step {step}"
