@@ -3,12 +3,13 @@
 // Algorithm 1; next-layer prediction of Sec. III observation 3 / Sec. IV-C,
 // which is the same computation with the next layer's gate on the same x).
 //
-// Prefill-size calls: one wavefront owns one token.  The lanes split the hidden
-// dimension in 16-byte pieces, keep one fp32 partial sum per expert, and fold
-// the partials with a butterfly of wavefront shuffles, after which every lane
-// holds all E logits and the softmax / top-k run redundantly in registers.  Up
-// to two gates (this layer's and the next layer's) are evaluated per token so x
-// comes from HBM once; the second pass over the row hits the vector cache.
+// Prefill-size calls, bf16 storage: a 16-token x 16-expert MFMA tile per
+// workgroup with the hidden dimension split over 16 wavefronts
+// (route_mfma_kernel); x comes from HBM once for both this layer's and the next
+// layer's gate.  fp32 storage (the small parity configuration) keeps a plain
+// kernel: one wavefront owns one token, the lanes split the hidden dimension
+// in 16-byte pieces with one fp32 partial sum per expert, folded by a butterfly
+// of wavefront shuffles, and the softmax / top-k run redundantly in registers.
 //
 // Decode-size calls (at most 16 tokens) are a chain of memory latencies rather
 // than a stream: one workgroup routes the whole call with the hidden dimension
@@ -142,6 +143,108 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p) {
             if (p.gate[g].hist != nullptr) p.gate[g].hist[(size_t)blockIdx.x * E + tid] = hist[g][tid];
 }
 
+// bf16 storage: the gate GEMM on the matrix cores.  One workgroup of 16 wavefronts owns 16 tokens:
+// they are the 16 rows of a v_mfma_f32_16x16x32_bf16 whose 16 columns are a block of 16 experts,
+// and the wavefronts split the hidden dimension in contiguous runs of 32-element steps.  x is the
+// streamed operand (each byte read once, 8 steps of it kept in registers while all gates and expert
+// blocks are applied); the gate rows come from cache, once per 16 tokens.  The wavefronts' partial
+// 16 x 16 tiles are summed in wavefront order through LDS, gate by gate; then wavefront i takes
+// token i with expert e on lane e for the softmax and the top-k.
+// NBG = number of 16-expert blocks per gate.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+template <int NBG>
+__global__ __launch_bounds__(1024) void route_mfma_kernel(RouteParams p) {
+    constexpr int kChunk = NBG == 1 ? 8 : 4;  // K steps whose x fragments are held in registers at a time
+    __shared__ int hist[2][64];
+    __shared__ f32x4 part[16][NBG][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 128) hist[tid >> 6][tid & 63] = 0;
+    const int H = p.hidden, E = p.n_experts, T = p.tokens;
+    const int t0 = blockIdx.x * kRouteTokensPerBlock;
+    const int row = lane & 15, kq = lane >> 4;
+    const uint16_t* x = static_cast<const uint16_t*>(p.x);
+    const bool xrow_on = t0 + row < T;
+    const uint16_t* xrow = x + (size_t)(xrow_on ? t0 + row : 0) * H + kq * 8;
+
+    const int k_steps = H / 32;
+    const int per = (k_steps + 15) / 16;
+    const int s_begin = wave * per;
+    const int s_end = min(k_steps, s_begin + per);
+
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[2][NBG];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int nb = 0; nb < NBG; ++nb) acc[g][nb] = zero;
+
+    for (int s0 = s_begin; s0 < s_end; s0 += kChunk) {
+        u32x4 xa[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            xa[i] = u32x4{0u, 0u, 0u, 0u};
+            if (xrow_on && s0 + i < s_end) xa[i] = *reinterpret_cast<const u32x4*>(xrow + (size_t)(s0 + i) * 32);
+        }
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            if (g < p.n_gates) {
+                const uint16_t* wg = static_cast<const uint16_t*>(p.gate[g].w);
+#pragma unroll
+                for (int nb = 0; nb < NBG; ++nb) {
+                    const int e = nb * 16 + row;  // this lane's column of the B operand
+                    const uint16_t* wrow = wg + (size_t)(e < E ? e : 0) * H + kq * 8;
+                    u32x4 wb[kChunk];
+#pragma unroll
+                    for (int i = 0; i < kChunk; ++i) {
+                        wb[i] = u32x4{0u, 0u, 0u, 0u};
+                        if (e < E && s0 + i < s_end)
+                            wb[i] = *reinterpret_cast<const u32x4*>(wrow + (size_t)(s0 + i) * 32);
+                    }
+#pragma unroll
+                    for (int i = 0; i < kChunk; ++i)
+                        acc[g][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, xa[i]),
+                                                                             __builtin_bit_cast(bf16x8, wb[i]),
+                                                                             acc[g][nb], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // MFMA result: lane holds column (expert in block) lane & 15 and rows (tokens) 4 * (lane / 16) + r.
+    const int t = t0 + wave;  // the token this wavefront selects for
+    for (int g = 0; g < p.n_gates; ++g) {
+        __syncthreads();  // hist is cleared / the previous gate's partial tiles have been read
+#pragma unroll
+        for (int nb = 0; nb < NBG; ++nb) part[wave][nb][lane] = g == 0 ? acc[0][nb] : acc[1][nb];
+        __syncthreads();
+        if (t < T) {
+            float z = -INFINITY;
+            if (lane < E) {
+                const int nb = lane >> 4, src = (wave >> 2) * 16 + (lane & 15), r = wave & 3;
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < 16; ++w) sum += part[w][nb][src][r];
+                z = sum + (p.gate[g].bias != nullptr ? p.gate[g].bias[lane] : 0.f);
+            }
+            int my_sel;
+            float my_w;
+            select_topk_lanes(z, lane, E, p.top_k, my_sel, my_w);
+            if (lane < p.top_k) {
+                p.gate[g].idx[(size_t)t * p.top_k + lane] = my_sel;
+                if (p.gate[g].wts != nullptr) p.gate[g].wts[(size_t)t * p.top_k + lane] = my_w;
+                atomicAdd(&hist[g][my_sel], 1);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < E)
+        for (int g = 0; g < p.n_gates; ++g)
+            if (p.gate[g].hist != nullptr) p.gate[g].hist[(size_t)blockIdx.x * E + tid] = hist[g][tid];
+}
+
 // One workgroup routes a decode-size call against up to two gates and writes indices, weights
 // and counts.
 template <typename scalar_t>
@@ -196,8 +299,11 @@ RouteParams make_params(const moe_shape_t& s, int tokens, const void* x, const G
 hipError_t launch_route(const moe_shape_t& s, int tokens, const void* x, const GateArgs* gates, int n_gates,
                         hipStream_t stream) {
     RouteParams p = make_params(s, tokens, x, gates, n_gates);
+    const int grid = route_blocks(tokens);
     if (s.dtype == MOE_F32) launch_by_epad<float>(p, stream);
-    else launch_by_epad<uint16_t>(p, stream);
+    else if (s.n_experts <= 16) route_mfma_kernel<1><<<grid, 1024, 0, stream>>>(p);
+    else if (s.n_experts <= 32) route_mfma_kernel<2><<<grid, 1024, 0, stream>>>(p);
+    else route_mfma_kernel<4><<<grid, 1024, 0, stream>>>(p);
     return hipGetLastError();
 }
 

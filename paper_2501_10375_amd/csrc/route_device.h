@@ -39,6 +39,36 @@ __device__ inline float wave_sum(float v) {
     return v;
 }
 
+// Softmax over the E logits held one per lane (z of lane e is expert e's logit, -inf beyond E),
+// then k passes of arg-max across the lanes, the lowest lane among equals winning.  Every lane
+// takes part; on return lane j < k holds selection j (expert and renormalised weight), in
+// descending probability.
+__device__ inline void select_topk_lanes(float z, int lane, int E, int k, int& my_sel, float& my_w) {
+    const float zmax = wave_max(z);
+    float p = lane < E ? expf(z - zmax) : 0.f;
+    p = p / wave_sum(p);
+    bool taken = lane >= E;
+    float my_p = 0.f, wsum = 0.f;
+    my_sel = 0;
+    for (int j = 0; j < k; ++j) {
+        const float cand = taken ? -1.f : p;
+        float best = wave_max(cand);
+        uint64_t m = __ballot(!taken && cand == best);
+        if (m == 0) {  // only with non-finite inputs: still select a valid, distinct expert
+            m = __ballot(!taken);
+            best = 0.f;
+        }
+        const int sel = __ffsll((long long)m) - 1;
+        if (lane == sel) taken = true;
+        if (lane == j) {
+            my_sel = sel;
+            my_p = best;
+        }
+        wsum += best;
+    }
+    my_w = my_p / wsum;
+}
+
 // ---- routing of a decode-size call (at most 16 tokens) by one workgroup of 8 wavefronts ----
 
 constexpr int kSmallRouteThreads = 512;
@@ -142,32 +172,12 @@ __device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const sca
             for (int w = 0; w < 8; ++w) s += part[(w * T + t) * 64 + lane];
             z = s + my_bias;
         }
-        const float zmax = wave_max(z);
-        float p = lane < E ? expf(z - zmax) : 0.f;
-        p = p / wave_sum(p);
-        // k passes of arg-max across the lanes; the lowest lane among equals wins
-        bool taken = lane >= E;
-        int my_sel = 0;
-        float my_p = 0.f, wsum = 0.f;
-        for (int j = 0; j < k; ++j) {
-            const float cand = taken ? -1.f : p;
-            float best = wave_max(cand);
-            uint64_t m = __ballot(!taken && cand == best);
-            if (m == 0) {  // only with non-finite inputs: still select a valid, distinct expert
-                m = __ballot(!taken);
-                best = 0.f;
-            }
-            const int sel = __ffsll((long long)m) - 1;
-            if (lane == sel) taken = true;
-            if (lane == j) {
-                my_sel = sel;
-                my_p = best;
-            }
-            wsum += best;
-        }
+        int my_sel;
+        float my_w;
+        select_topk_lanes(z, lane, E, k, my_sel, my_w);
         if (lane < k) {
             sm.idx[t * k + lane] = my_sel;
-            sm.w[t * k + lane] = my_p / wsum;
+            sm.w[t * k + lane] = my_w;
         }
     }
     __syncthreads();
