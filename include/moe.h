@@ -15,8 +15,11 @@
  * Conventions common to every entry point
  *   - All tensor pointers are DEVICE pointers on the current HIP device, dense
  *     row-major with the last index contiguous, 16-byte aligned.  The caller
- *     owns every buffer, including the workspace; the library keeps no state
- *     and allocates nothing.
+ *     owns every buffer, including the workspace; the library allocates
+ *     nothing and keeps no state apart from a process-wide launch counter.
+ *     The workspace is scratch: its contents never need initialising and are
+ *     undefined afterwards.  Two calls that use the same workspace must not
+ *     run at the same time (order them on one stream or with events).
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
  *     stream).  Calls validate their arguments on the host, enqueue kernels on
  *     that stream and return without synchronising.  Outputs are valid once
@@ -33,6 +36,12 @@
  *   - Expert selection: softmax over all experts in fp32, the top_k largest
  *     probabilities in descending order (equal probabilities: lower expert
  *     index first), their weights renormalised to sum to one.
+ *   - Two kernels are persistent (one workgroup per compute unit) and make
+ *     their workgroups wait for one another: the grouped GEMM of prefill-size
+ *     bf16 calls and the single kernel of bf16 calls with at most 16 tokens.
+ *     Every such wait is bounded, so a call always ends; the result is only
+ *     defined when the device can hold the whole grid at once, i.e. when no
+ *     other kernel occupies compute units for the duration of the call.
  *   - Determinism: no floating-point atomics are used; two calls on the same
  *     inputs give bitwise identical outputs.  moe_layer gives bitwise the same
  *     outputs as moe_route (+ moe_predict_next) followed by moe_expert_ffn.

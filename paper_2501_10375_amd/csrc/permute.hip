@@ -50,17 +50,27 @@ __global__ __launch_bounds__(256) void finalize_kernel(const int32_t* __restrict
         before[tid] = 0;
     }
     __syncthreads();
-    {
-        const int e = tid & 63, part = tid >> 6;
-        if (e < E) {
-            int tot = 0, bef = 0;
-            for (int b = part; b < n_blocks; b += 4) {
-                const int v = hist[(size_t)b * E + e];
-                tot += v;
-                if (b < blk) bef += v;
+    // Coalesced sweep over all block histograms (integer sums, so the order is immaterial).  When E
+    // divides the workgroup size a thread always meets the same expert and sums in registers.
+    const int n_cells = n_blocks * E;
+    const int my_first = blk * E;
+    if (256 % E == 0) {
+        int tot = 0, bef = 0;
+#pragma unroll 4
+        for (int i = tid; i < n_cells; i += 256) {
+            const int v = hist[i];
+            tot += v;
+            bef += i < my_first ? v : 0;
+        }
+        if (tot != 0) atomicAdd(&total[tid % E], tot);
+        if (bef != 0) atomicAdd(&before[tid % E], bef);
+    } else {
+        for (int i = tid; i < n_cells; i += 256) {
+            const int v = hist[i];
+            if (v != 0) {
+                atomicAdd(&total[i % E], v);
+                if (i < my_first) atomicAdd(&before[i % E], v);
             }
-            atomicAdd(&total[e], tot);
-            atomicAdd(&before[e], bef);
         }
     }
     __syncthreads();

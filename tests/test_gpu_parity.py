@@ -36,6 +36,7 @@ def test_config0_tiny_fp32_layer(oracle):
     (17, 256, 512, 8, 2),      # just above the decode threshold
     (90, 192, 128, 32, 3),     # two 16-expert blocks in the router
     (40, 8192, 128, 8, 2),     # hidden dimension longer than one register chunk of the router
+    (60, 128, 128, 12, 3),     # expert count that is not a power of two
 ])
 def test_bf16_prefill_path(oracle, T, H, F, E, k):
     d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
@@ -46,6 +47,7 @@ def test_bf16_prefill_path(oracle, T, H, F, E, k):
 @pytest.mark.parametrize("T,H,F,E,k", [
     (1, 256, 512, 8, 2), (5, 256, 512, 8, 2), (16, 256, 512, 8, 2), (8, 512, 1600, 16, 2), (3, 64, 64, 4, 1),
     (16, 128, 320, 8, 8), (7, 2048, 1024, 8, 2), (4, 128, 128, 64, 8), (9, 192, 256, 32, 2), (6, 8192, 128, 8, 2),
+    (5, 128, 128, 6, 2),
 ])
 def test_bf16_decode_path(oracle, T, H, F, E, k):
     d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
