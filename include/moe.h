@@ -36,12 +36,13 @@
  *   - Expert selection: softmax over all experts in fp32, the top_k largest
  *     probabilities in descending order (equal probabilities: lower expert
  *     index first), their weights renormalised to sum to one.
- *   - Two kernels are persistent (one workgroup per compute unit) and make
- *     their workgroups wait for one another: the grouped GEMM of prefill-size
- *     bf16 calls and the single kernel of bf16 calls with at most 16 tokens.
- *     Every such wait is bounded, so a call always ends; the result is only
- *     defined when the device can hold the whole grid at once, i.e. when no
- *     other kernel occupies compute units for the duration of the call.
+ *   - bf16 calls with at most 16 tokens run as one persistent kernel (one
+ *     workgroup per compute unit) whose workgroups wait for one another
+ *     between the two expert GEMMs.  The wait is bounded, so a call always
+ *     ends, but its result is only defined when the device can hold the whole
+ *     grid at once, i.e. when no other kernel occupies compute units for the
+ *     duration of the call.  (The prefill-size grouped GEMM is persistent too;
+ *     its waits only tune timing and never affect results.)
  *   - Determinism: no floating-point atomics are used; two calls on the same
  *     inputs give bitwise identical outputs.  moe_layer gives bitwise the same
  *     outputs as moe_route (+ moe_predict_next) followed by moe_expert_ffn.
