@@ -43,7 +43,14 @@ __device__ inline float wave_sum(float v) {
 // then k passes of arg-max across the lanes, the lowest lane among equals winning.  Every lane
 // takes part; on return lane j < k holds selection j (expert and renormalised weight), in
 // descending probability.
-__device__ inline void select_topk_lanes(float z, int lane, int E, int k, int& my_sel, float& my_w) {
+//
+// With `degrade` (graceful degradation, Sec. IV-C "Accuracy Stabilization" / "Graceful
+// Degradation"; `resident` = this lane's expert is in the GPU expert cache): if no selected expert
+// is resident, the last selection (the lowest probability) is replaced by the most probable
+// resident expert, if there is one; it cannot outrank the k - 1 selections that stay, so the
+// order is preserved.
+__device__ inline void select_topk_lanes(float z, int lane, int E, int k, int& my_sel, float& my_w,
+                                         bool degrade = false, bool resident = false) {
     const float zmax = wave_max(z);
     float p = lane < E ? expf(z - zmax) : 0.f;
     p = p / wave_sum(p);
@@ -65,6 +72,22 @@ __device__ inline void select_topk_lanes(float z, int lane, int E, int k, int& m
             my_p = best;
         }
         wsum += best;
+    }
+    if (degrade) {
+        const bool selected = taken && lane < E;
+        if (__ballot(selected && resident) == 0) {
+            const bool cand = !taken && resident;
+            const float best = wave_max(cand ? p : -1.f);
+            const uint64_t m = __ballot(cand && p == best);
+            if (m != 0) {
+                if (lane == k - 1) {
+                    my_sel = __ffsll((long long)m) - 1;
+                    my_p = best;
+                }
+                wsum = 0.f;
+                for (int j = 0; j < k; ++j) wsum += __shfl(my_p, j, 64);
+            }
+        }
     }
     my_w = my_p / wsum;
 }
@@ -114,6 +137,7 @@ __device__ inline float reduce8_scatter(const float (&acc)[8], int lane) {
 // renormalised weight of selection j of token t, in descending probability, ties to the lower
 // index.  The arithmetic depends only on (T, H, E, k), never on the workgroup, so any number of
 // workgroups computing the same call agree bit for bit.  `part` is kRoutePartFloats of LDS.
+// With `on_gpu` (uint8 [E]) the selection is degraded gracefully, see select_topk_lanes.
 //
 // The 8 wavefronts split the hidden dimension in interleaved 512-element chunks, so the gate and
 // x are read once per workgroup whatever T is; a wavefront walks the tokens two at a time over
@@ -123,10 +147,11 @@ __device__ inline float reduce8_scatter(const float (&acc)[8], int lane) {
 template <typename scalar_t>
 __device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const scalar_t* __restrict__ wg,
                                        const float* __restrict__ bias, int T, int H, int E, int k, RouteSmem& sm,
-                                       float* part) {
+                                       float* part, const uint8_t* __restrict__ on_gpu = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // requested first so that it arrives together with the gate rows
     const float my_bias = (bias != nullptr && lane < E) ? bias[lane] : 0.f;
+    const bool resident = on_gpu != nullptr && lane < E && on_gpu[lane] != 0;
     const int n_blocks = (E + 7) / 8;
     const int esub = ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
     for (int t = 0; t < T; t += 2) {
@@ -174,7 +199,7 @@ __device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const sca
         }
         int my_sel;
         float my_w;
-        select_topk_lanes(z, lane, E, k, my_sel, my_w);
+        select_topk_lanes(z, lane, E, k, my_sel, my_w, on_gpu != nullptr, resident);
         if (lane < k) {
             sm.idx[t * k + lane] = my_sel;
             sm.w[t * k + lane] = my_w;

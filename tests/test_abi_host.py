@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "moe.h")
+POLICY_HEADER = os.path.join(ROOT, "include", "daop_policy.h")
 
 
 @pytest.fixture(scope="module")
@@ -19,10 +20,10 @@ def L():
     return moe.lib()
 
 
-def _declared_functions():
-    text = open(HEADER).read()
+def _declared_functions(header=HEADER, prefix="moe_"):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_]+)\s*\(", text)))
 
 
 def test_header_declares_the_four_entry_points():
@@ -37,6 +38,33 @@ def test_library_exports_every_declared_symbol(L):
     for name in _declared_functions():
         assert hasattr(L, name), name
     assert set(moe.EXPORTS) == set(_declared_functions())
+    from paper_2501_10375_amd import policy
+
+    declared = _declared_functions(POLICY_HEADER, "daop_")
+    assert len(declared) == 4
+    for name in declared:
+        assert hasattr(L, name), name
+    assert set(policy.EXPORTS) == set(declared)
+
+
+def test_policy_calls_reject_bad_arguments_on_the_host(L):
+    from paper_2501_10375_amd import moe, policy
+
+    P = policy.lib()
+    fake = ctypes.c_void_p(0x1000)   # aligned, never dereferenced: validation fails first
+    assert P.daop_similarity(0, 8, fake, fake, fake, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_similarity(4, 65, fake, fake, fake, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_similarity(4, 8, None, fake, fake, None) == moe.MOE_ERR_NULL
+    assert P.daop_similarity(4, 8, ctypes.c_void_p(0x1004), fake, fake, None) == moe.MOE_ERR_ALIGN
+    assert P.daop_plan_swaps(4, 8, fake, fake, -1.0, None, None, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_plan_swaps(4, 8, fake, fake, float("nan"), None, None, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_plan_swaps(4, 8, fake, None, 1.05, None, None, None) == moe.MOE_ERR_NULL
+    assert P.daop_memory_init(2000, 8, fake, 3, fake, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_memory_init(4, 8, None, 3, fake, None) == moe.MOE_ERR_NULL
+    s = _shape()
+    assert P.daop_predict_degraded(ctypes.byref(s), 4, fake, fake, None, None, fake, None, None) == moe.MOE_ERR_NULL
+    assert P.daop_predict_degraded(ctypes.byref(s), -1, fake, fake, None, fake, fake, None, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_predict_degraded(ctypes.byref(s), 0, None, fake, None, fake, None, None, None) == moe.MOE_OK
 
 
 def test_status_strings(L):
