@@ -46,7 +46,85 @@ def parse():
                     help="only run a plain device-to-device copy of this many MiB three times (reference for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle is timed on (0 = pick for ~15 s)")
+    ap.add_argument("--workload", default="layer", choices=["layer", "stack"],
+                    help="layer: the headline single-layer benchmark; stack: a resident stack of layers, "
+                         "one prefill then single-token decode steps (prints its own JSON line)")
+    ap.add_argument("--stack-layers", type=int, default=32)
+    ap.add_argument("--stack-prefill", type=int, default=1024)
+    ap.add_argument("--stack-decode-steps", type=int, default=128)
     return ap.parse_args()
+
+
+def run_stack(args):
+    """32 resident Mixtral-shaped layers: prefill of one sequence, then decode steps of one token."""
+    import torch
+    from paper_2501_10375_amd import moe, policy, stack, synth
+
+    cfg = WORKLOADS[args.model]
+    H, F, E, k = cfg["H"], cfg["F"], cfg["E"], cfg["k"]
+    L, T, steps = args.stack_layers, args.stack_prefill, args.stack_decode_steps
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    st = stack.MoeStack(L, H, F, E, k, torch.bfloat16, dev, zipf_s=cfg["zipf"], max_tokens=max(T, 1))
+    torch.cuda.synchronize()
+
+    def timed(fn, calls):
+        torch.cuda.synchronize()
+        moe.moe_stage_timing_begin(calls)
+        t0 = time.perf_counter()
+        r = fn()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        stages = moe.moe_stage_timing_end()
+        gpu_ms = sum(ms * n for ms, n in stages.values())
+        return r, wall, gpu_ms
+
+    h0 = synth.normal((T, H), 999, synth.TID_X, 1.0, torch.float32, dev)
+    st.forward(h0, st.new_counts())   # warm-up
+    prefill = st.new_counts()
+    out, p_wall, p_gpu_ms = timed(lambda: st.forward(h0, prefill), L)
+    exact, overlap = stack.agreement(out["pred"].clone(), out["idx"].clone())
+
+    hs = [synth.normal((1, H), 1000 + s, synth.TID_X, 1.0, torch.float32, dev) for s in range(steps)]
+    decode = st.new_counts()
+    d_exact = torch.zeros(L - 1, dtype=torch.float64, device=dev)
+
+    def decode_loop():
+        for h in hs:
+            o = st.forward(h, decode)
+            e, _ = stack.agreement(o["pred"], o["idx"])
+            d_exact.add_(e)
+
+    st.forward(hs[0], st.new_counts())
+    _, d_wall, d_gpu_ms = timed(decode_loop, L * steps)
+    P, D = prefill[:, :E].contiguous(), decode[:, :E].contiguous()
+    sim, per = policy.daop_similarity(P, D)
+    cache = policy.daop_memory_init(D, (L * E * 15) // 32)      # expert cache ratio 46.875 %
+    resident_before = (P * cache.int()).sum().item() / P.sum().item()
+    _, n_swaps = policy.daop_plan_swaps(P, cache)
+    resident_after = (P * cache.int()).sum().item() / P.sum().item()
+    dec_bytes = steps * L * (2 * 3.0 * H * F * 2)   # two experts per token and layer
+    print(json.dumps({
+        "metric": "moe_stack_decode_tokens_per_s", "value": steps / (d_gpu_ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.model}_stack_{L}_layers_prefill_T{T}_then_{steps}_decode_steps", "layers": L,
+                   "hidden": H, "ffn": F, "n_experts": E, "top_k": k, "weights_GB": st.weight_bytes() / 1e9,
+                   "glue": "parameter-free RMS norm + residual in torch between the layers (stand-in for attention)"},
+        "prefill": {"tokens": T, "moe_gpu_ms": p_gpu_ms, "wall_ms": p_wall * 1e3, "tokens_per_s_moe_gpu_time": T / (p_gpu_ms * 1e-3),
+                    "tflops_moe_gpu_time": L * T * 12.0 * H * F / (p_gpu_ms * 1e-3) / 1e12},
+        "decode": {"steps": steps, "moe_gpu_ms": d_gpu_ms, "wall_ms": d_wall * 1e3,
+                   "tokens_per_s_moe_gpu_time": steps / (d_gpu_ms * 1e-3), "tokens_per_s_wall": steps / d_wall,
+                   "GBps_moe_gpu_time": dec_bytes / (d_gpu_ms * 1e-3) / 1e9,
+                   "frac_of_hbm_peak_moe_gpu_time": dec_bytes / (d_gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "prediction_agreement": {"prefill_exact_set_mean": exact.mean().item(), "prefill_overlap_mean": overlap.mean().item(),
+                                 "prefill_exact_set_layers_ge_4": exact[3:].mean().item() if L > 4 else None,
+                                 "decode_exact_set_mean": (d_exact / steps).mean().item()},
+        "eq1_similarity_prefill_vs_decode": sim.item(),
+        "algorithm1": {"cache_slots": int(cache.sum().item()), "swaps": int(n_swaps.sum().item()),
+                       "prefill_tokens_on_resident_experts_before": resident_before,
+                       "prefill_tokens_on_resident_experts_after": resident_after},
+        "prefill_counts_first_layers": P[:2].cpu().tolist(),
+    }))
 
 
 def time_steps(fn, steps, warmup):
@@ -105,6 +183,9 @@ def main():
 
     moe.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "stack":
+        run_stack(args)
+        return
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = WORKLOADS[args.model]

@@ -1,0 +1,74 @@
+"""The multi-layer harness (paper_2501_10375_amd/stack.py): teacher-forced per-layer parity with the
+oracle (each layer's oracle sees the GPU's actual layer input, because bf16 drift through a stack
+legitimately changes selections), count matrices, agreement rates and Eq. 1."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_10375_amd import moe, policy, stack, synth
+from parity_util import check_layer, host
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def test_small_stack_teacher_forced_parity(oracle):
+    from oracle import daop_policy as pol
+
+    L, H, F, E, k, T = 4, 256, 512, 8, 2, 40
+    st = stack.MoeStack(L, H, F, E, k, torch.bfloat16, DEV, zipf_s=1.2, max_tokens=T)
+    h0 = synth.normal((T, H), 500, synth.TID_X, 1.0, torch.float32, DEV)
+    prefill = st.new_counts()
+    out = st.forward(h0, prefill, keep_inputs=True, keep_outputs=True)
+    torch.cuda.synchronize()
+    idx = out["idx"].clone()
+    pred = out["pred"].clone()
+    excluded = 0
+    ref_idx = []
+    for l in range(L):
+        d = dict(st.layers[l], x=out["inputs"][l])
+        nxt = st.layers[l + 1] if l + 1 < L else None
+        d["wg_next"], d["bias_next"] = (nxt["wg"], nxt["bias"]) if nxt else (None, None)
+        y, w = out["outputs"][l]
+        res = {"y": y, "idx": idx[l], "w": w, "counts": prefill[l, :E], "pred_idx": pred[l] if nxt else None}
+        r = check_layer(oracle, d, st.shape, res, torch.bfloat16, label=f"stack layer {l}", predict=nxt is not None)
+        excluded += r["excluded"] + r["excluded_pred"]
+        hd = host(d)
+        ref_idx.append(oracle.route(hd["x"], hd["wg"], hd["bias"], k)["idx"])
+    assert excluded <= 2
+    assert prefill[:, :E].sum(1).tolist() == [T * k] * L
+
+    # agreement rates: the harness's numbers equal the ones recomputed on the host from its own outputs,
+    # and the oracle's (teacher-forced) unless a near-tie token was excluded
+    exact, overlap = stack.agreement(pred, idx)
+    pi, ai = pred.cpu().numpy(), idx.cpu().numpy()
+    for l in range(L - 1):
+        same = [set(pi[l, t]) == set(ai[l + 1, t]) for t in range(T)]
+        ov = [len(set(pi[l, t]) & set(ai[l + 1, t])) / k for t in range(T)]
+        assert abs(exact[l].item() - np.mean(same)) < 1e-12 and abs(overlap[l].item() - np.mean(ov)) < 1e-12
+    assert 0.0 <= exact.min().item() and overlap.max().item() <= 1.0
+
+    # decode steps accumulate into their own count matrix; Eq. 1 between the two matrices
+    decode = st.new_counts()
+    for step in range(6):
+        h = synth.normal((1, H), 1000 + step, synth.TID_X, 1.0, torch.float32, DEV)
+        st.forward(h, decode)
+    torch.cuda.synchronize()
+    assert decode[:, :E].sum(1).tolist() == [6 * k] * L
+    P = prefill[:, :E].contiguous()
+    D = decode[:, :E].contiguous()
+    sim, per = policy.daop_similarity(P, D)
+    ref_sim, ref_per = pol.similarity(P.cpu().numpy(), D.cpu().numpy())
+    assert abs(sim.item() - ref_sim) < 1e-14 and np.allclose(per.cpu().numpy(), ref_per, atol=1e-15)
+
+    # the counts drive Algorithm 1: plan on the prefill counts from a calibrated cache of half the experts
+    cache = policy.daop_memory_init(D, L * E // 2)
+    before = cache.clone()
+    swaps, n = policy.daop_plan_swaps(P, cache)
+    torch.cuda.synchronize()
+    ref_swaps, ref_mask = pol.plan_swaps_all(P.cpu().numpy(), before.cpu().numpy())
+    assert np.array_equal(cache.cpu().numpy().astype(bool), ref_mask)
+    assert n.cpu().tolist() == [len(s) for s in ref_swaps]
+    covered_before = (P * before.int()).sum().item()
+    covered_after = (P * cache.int()).sum().item()
+    assert covered_after >= covered_before   # more prefill tokens hit GPU-resident experts after the swaps
