@@ -76,9 +76,11 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kMaxTok = kDecodeMaxTokens;
-static_assert(kMaxTok == 16, "an expert's tokens are the 16 columns of one 16x16x32 MFMA");
-static_assert(kThreads == kSmallRouteThreads && kMaxTok == kSmallRouteMaxTokens, "routing runs in the same workgroup");
+// An expert's tokens are the columns of 16x16x32 MFMAs: NC column groups of 16 serve calls of up to
+// 16 * NC tokens (a token selects an expert at most once, so no expert sees more tokens than the call has).
+static_assert(kStreamMaxTokens == 32, "column groups are instantiated for 16 and 32 tokens");
+static_assert(kThreads == kSmallRouteThreads && kDecodeMaxTokens == kSmallRouteMaxTokens,
+              "in-kernel routing runs in the same workgroup");
 
 struct DecodeArgs {
     const uint16_t* x;      // [T, H]
@@ -100,16 +102,20 @@ struct DecodeArgs {
     int T, k, E, H, F;
 };
 
+template <int NC>
 struct Groups {
+    static constexpr int kMaxTok = 16 * NC;
     int n_active;
     int expert[64];           // active experts, ascending id
-    int cnt[64];              // tokens of that expert (<= 16)
+    int cnt[64];              // tokens of that expert (<= 16 * NC)
     int assign[64][kMaxTok];  // their assignment ids t*k + j, ascending
 };
 
 // Builds the per-expert token lists from the selections in LDS; call with all threads, ends with
 // a barrier.
-__device__ void build_groups(Groups& g, const int* idx, int A, int E) {
+template <int NC>
+__device__ void build_groups(Groups<NC>& g, const int* idx, int A, int E) {
+    constexpr int kMaxTok = Groups<NC>::kMaxTok;
     const int tid = threadIdx.x;
     if (tid < 64) {
         int c = 0;
@@ -181,18 +187,23 @@ struct LaneMap {
     }
 };
 
+template <int NC>
 struct Smem {
-    RouteSmem route;
-    Groups g;
-    f32x4 red[2][kWaves][2][64];
-    float yacc[kMaxTok][16];
+    int idx[16 * NC * 8];     // selections of the call (expert per assignment) ...
+    float w[16 * NC * 8];     // ... and their weights
+    RouteSmem route;          // scratch of the in-kernel routing (NC == 1 only)
+    Groups<NC> g;
+    // partial tiles of the 8 wavefronts; double-buffered over consecutive tiles while that fits
+    static constexpr int kRedBufs = NC >= 4 ? 1 : 2;
+    f32x4 red[kRedBufs][kWaves][2][NC][64];
+    float yacc[16 * NC][16];
 };
 
 // ---- phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f]) over this workgroup's share
 // of the (active expert, 16-feature tile) list.
-template <int P>
-__device__ inline void gemm1_phase(const DecodeArgs& p, Smem& sm) {
-    const Groups& g = sm.g;
+template <int P, int NC>
+__device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
+    const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
     const LaneMap lm(lane);
@@ -213,11 +224,11 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem& sm) {
     const int spt = (per + P - 1) / P * P;  // steps per tile, padded to the pipeline depth
     const long total_q = (long)(t1 - t0) * spt;
 
-    u32x4 lo1[P], hi1[P], lo3[P], hi3[P], xa[P], xb[P];
+    u32x4 lo1[P], hi1[P], lo3[P], hi3[P], xa[P][NC], xb[P][NC];
     // Issue-side state: the next step to request and the row bases of its tile.
     int is = 0, itile = t0;
-    size_t wlo = 0, whi = 0, xbase = 0;
-    bool xcol = false;
+    size_t wlo = 0, whi = 0, xbase[NC];
+    bool xcol[NC];
     auto enter_tile = [&]() {
         const int d = itile / tiles_per_expert;
         const int f0 = (itile - d * tiles_per_expert) * 16;
@@ -225,8 +236,11 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem& sm) {
         const size_t k0 = (size_t)s_begin * 64;
         wlo = (row0 + lm.row_lo) * H + k0 + lm.k_lo;
         whi = (row0 + lm.row_hi) * H + k0 + lm.k_hi;
-        xcol = col < g.cnt[d];
-        xbase = (size_t)(xcol ? g.assign[d][col] / k : 0) * H + k0 + lm.kq8;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            xcol[c] = col + 16 * c < g.cnt[d];
+            xbase[c] = (size_t)(xcol[c] ? g.assign[d][col + 16 * c] / k : 0) * H + k0 + lm.kq8;
+        }
     };
     enter_tile();
     auto issue = [&](int i) {
@@ -235,8 +249,11 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem& sm) {
         hi1[i] = load16(p.w1 + whi + is * 64, on);
         lo3[i] = load16(p.w3 + wlo + is * 64, on);
         hi3[i] = load16(p.w3 + whi + is * 64, on);
-        xa[i] = load16(p.x + xbase + is * 64, on && xcol);
-        xb[i] = load16(p.x + xbase + is * 64 + 32, on && xcol);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            xa[i][c] = load16(p.x + xbase[c] + is * 64, on && xcol[c]);
+            xb[i][c] = load16(p.x + xbase[c] + is * 64 + 32, on && xcol[c]);
+        }
         if (++is == spt) {
             is = 0;
             if (++itile < t1) enter_tile();
@@ -246,63 +263,202 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem& sm) {
     for (int i = 0; i < P; ++i) issue(i);  // total_q >= spt >= P
 
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    f32x4 g1 = zero, g2 = zero, u1 = zero, u2 = zero;
+    f32x4 g1[NC], g2[NC], u1[NC], u2[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
     int cs = 0, ctile = t0;
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            const bf16x8 b1 = __builtin_bit_cast(bf16x8, xa[i]);
-            const bf16x8 b2 = __builtin_bit_cast(bf16x8, xb[i]);
-            g1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, hi1[i], lo1[i]), b1, g1, 0, 0, 0);
-            g2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo1[i], hi1[i]), b2, g2, 0, 0, 0);
-            u1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, hi3[i], lo3[i]), b1, u1, 0, 0, 0);
-            u2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo3[i], hi3[i]), b2, u2, 0, 0, 0);
+            const bf16x8 a1 = pick(lm.upper, hi1[i], lo1[i]), a2 = pick(lm.upper, lo1[i], hi1[i]);
+            const bf16x8 a3 = pick(lm.upper, hi3[i], lo3[i]), a4 = pick(lm.upper, lo3[i], hi3[i]);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 b1 = __builtin_bit_cast(bf16x8, xa[i][c]);
+                const bf16x8 b2 = __builtin_bit_cast(bf16x8, xb[i][c]);
+                g1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, g1[c], 0, 0, 0);
+                g2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b2, g2[c], 0, 0, 0);
+                u1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b1, u1[c], 0, 0, 0);
+                u2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a4, b2, u2[c], 0, 0, 0);
+            }
             if (q + P + i < total_q) issue(i);
         }
         cs += P;
         if (cs == spt) {
             // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
             // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
-            const int par = (ctile - t0) & 1;
-            sm.red[par][wave][0][lane] = fold_halves(g1, g2);
-            sm.red[par][wave][1][lane] = fold_halves(u1, u2);
+            const int par = (ctile - t0) % Smem<NC>::kRedBufs;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                sm.red[par][wave][0][c][lane] = fold_halves(g1[c], g2[c]);
+                sm.red[par][wave][1][c][lane] = fold_halves(u1[c], u2[c]);
+            }
             lds_barrier();
-            if (tid < 128) {
-                const int pl = tid & 63, rp = tid >> 6;  // features 2 * rp and 2 * rp + 1 of the lane's four
-                const int d = ctile / tiles_per_expert;
-                const int f0 = (ctile - d * tiles_per_expert) * 16;
-                const int c = pl & 15;
-                if (c < g.cnt[d]) {
+            const int d = ctile / tiles_per_expert;
+            const int f0 = (ctile - d * tiles_per_expert) * 16;
+            const int cnt = g.cnt[d];
+            // one reducer per (column group, lane, feature pair): 128 * NC work items
+            for (int item = tid; item < 128 * NC; item += kThreads) {
+                const int c = item >> 7, pl = item & 63, rp = (item >> 6) & 1;
+                const int tok = (pl & 15) + 16 * c;
+                if (tok < cnt) {
                     float o[2];
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         float gs = 0.f, us = 0.f;
 #pragma unroll
                         for (int w = 0; w < kWaves; ++w) {
-                            gs += sm.red[par][w][0][pl][2 * rp + h];
-                            us += sm.red[par][w][1][pl][2 * rp + h];
+                            gs += sm.red[par][w][0][c][pl][2 * rp + h];
+                            us += sm.red[par][w][1][c][pl][2 * rp + h];
                         }
                         o[h] = swiglu(gs, us);
                     }
                     // device-scope (write-through) store: read by other workgroups after the grid barrier
-                    uint32_t* dst = reinterpret_cast<uint32_t*>(p.act + (size_t)g.assign[d][c] * F + f0 +
+                    uint32_t* dst = reinterpret_cast<uint32_t*>(p.act + (size_t)g.assign[d][tok] * F + f0 +
                                                                 4 * (pl >> 4) + 2 * rp);
                     __hip_atomic_store(dst, pack_bf16x2(o[0], o[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            g1 = g2 = u1 = u2 = zero;
+            if (Smem<NC>::kRedBufs == 1) lds_barrier();  // the single buffer is free again
+#pragma unroll
+            for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
             cs = 0;
             ++ctile;
         }
     }
 }
 
+// ---- phase 1 when a wavefront's K slice is at most kXSteps steps (hidden <= 4096): the token
+// operand of an expert is the same for every feature tile, so its fragments are loaded once per
+// expert and stay in registers; only weights stream.  A tile is exactly kXSteps steps (statically
+// indexed fragments), steps past the slice multiply zeros.
+constexpr int kXSteps = 8;
+template <int P, int NC>
+__device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
+    static_assert(kXSteps % P == 0, "the weight ring must divide a tile");
+    const Groups<NC>& g = sm.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 15;
+    const LaneMap lm(lane);
+    const int H = p.H, F = p.F, k = p.k;
+
+    const int tiles_per_expert = F / 16;
+    const int total_tiles = g.n_active * tiles_per_expert;
+    const int tiles_per_wg = (total_tiles + gridDim.x - 1) / gridDim.x;
+    const int t0 = blockIdx.x * tiles_per_wg;
+    const int t1 = min(total_tiles, t0 + tiles_per_wg);
+
+    const int k_steps = H / 64;
+    const int per = (k_steps + kWaves - 1) / kWaves;  // <= kXSteps
+    const int s_begin = wave * per;
+    const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
+    const size_t k0 = (size_t)s_begin * 64;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    int par = 0;
+
+    for (int seg0 = t0; seg0 < t1;) {
+        const int d = seg0 / tiles_per_expert;
+        const int seg1 = min(t1, (d + 1) * tiles_per_expert);
+        const int cnt = g.cnt[d];
+        const size_t erow0 = (size_t)g.expert[d] * F;
+
+        // token fragments of this expert
+        u32x4 xr[kXSteps][NC][2];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const bool on = col + 16 * c < cnt;
+            const uint16_t* xp = p.x + (size_t)(on ? g.assign[d][col + 16 * c] / k : 0) * H + k0 + lm.kq8;
+#pragma unroll
+            for (int s = 0; s < kXSteps; ++s) {
+                xr[s][c][0] = load16(xp + s * 64, on && s < n_valid);
+                xr[s][c][1] = load16(xp + s * 64 + 32, on && s < n_valid);
+            }
+        }
+
+        // weight stream over the tiles [seg0, seg1), P steps ahead
+        u32x4 lo1[P], hi1[P], lo3[P], hi3[P];
+        int is = 0, itile = seg0;
+        auto issue = [&](int i) {
+            const int f0 = (itile - d * tiles_per_expert) * 16;
+            const size_t wlo = (erow0 + f0 + lm.row_lo) * H + k0 + lm.k_lo + is * 64;
+            const size_t whi = (erow0 + f0 + lm.row_hi) * H + k0 + lm.k_hi + is * 64;
+            const bool on = is < n_valid && itile < seg1;
+            lo1[i] = load16(p.w1 + wlo, on);
+            hi1[i] = load16(p.w1 + whi, on);
+            lo3[i] = load16(p.w3 + wlo, on);
+            hi3[i] = load16(p.w3 + whi, on);
+            if (++is == kXSteps) {
+                is = 0;
+                ++itile;
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < P; ++i) issue(i);
+
+        for (int ctile = seg0; ctile < seg1; ++ctile) {
+            f32x4 g1[NC], g2[NC], u1[NC], u2[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
+#pragma unroll
+            for (int s = 0; s < kXSteps; ++s) {
+                constexpr int kP = P;
+                const int i = s % kP;
+                const bf16x8 a1 = pick(lm.upper, hi1[i], lo1[i]), a2 = pick(lm.upper, lo1[i], hi1[i]);
+                const bf16x8 a3 = pick(lm.upper, hi3[i], lo3[i]), a4 = pick(lm.upper, lo3[i], hi3[i]);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    const bf16x8 b1 = __builtin_bit_cast(bf16x8, xr[s][c][0]);
+                    const bf16x8 b2 = __builtin_bit_cast(bf16x8, xr[s][c][1]);
+                    g1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, g1[c], 0, 0, 0);
+                    g2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b2, g2[c], 0, 0, 0);
+                    u1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b1, u1[c], 0, 0, 0);
+                    u2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a4, b2, u2[c], 0, 0, 0);
+                }
+                issue(i);  // requests past the segment's last tile are switched off inside
+            }
+            // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
+            // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                sm.red[par][wave][0][c][lane] = fold_halves(g1[c], g2[c]);
+                sm.red[par][wave][1][c][lane] = fold_halves(u1[c], u2[c]);
+            }
+            lds_barrier();
+            const int f0 = (ctile - d * tiles_per_expert) * 16;
+            for (int item = tid; item < 128 * NC; item += kThreads) {
+                const int c = item >> 7, pl = item & 63, rp = (item >> 6) & 1;
+                const int tok = (pl & 15) + 16 * c;
+                if (tok < cnt) {
+                    float o[2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        float gs = 0.f, us = 0.f;
+#pragma unroll
+                        for (int w = 0; w < kWaves; ++w) {
+                            gs += sm.red[par][w][0][c][pl][2 * rp + h];
+                            us += sm.red[par][w][1][c][pl][2 * rp + h];
+                        }
+                        o[h] = swiglu(gs, us);
+                    }
+                    // device-scope (write-through) store: read by other workgroups after the grid barrier
+                    uint32_t* dst = reinterpret_cast<uint32_t*>(p.act + (size_t)g.assign[d][tok] * F + f0 +
+                                                                4 * (pl >> 4) + 2 * rp);
+                    __hip_atomic_store(dst, pack_bf16x2(o[0], o[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            if (Smem<NC>::kRedBufs == 1) lds_barrier();
+            par = (par + 1) % Smem<NC>::kRedBufs;
+        }
+        seg0 = seg1;
+    }
+}
+
 // ---- phase 2: y[t, h] = sum over the token's experts (ascending expert id) of
 // w[a] * (act[a] . w2[e, h]) for this workgroup's 16-row tiles of h.  The first P steps of weight
 // loads are issued before the grid-wide barrier that `act` has to wait for.
-template <int P>
-__device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
-    const Groups& g = sm.g;
+template <int P, int NC>
+__device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
+    const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
     const LaneMap lm(lane);
@@ -326,7 +482,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
     if (tid == 0) __hip_atomic_store(&p.flags[blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (total_q == 0) return;
 
-    u32x4 lo[P], hi[P], aa[P], ab[P];
+    u32x4 lo[P], hi[P], aa[P][NC], ab[P][NC];
     // weight-side issue state
     int ws = 0, wd = 0, wt = blockIdx.x;
     size_t wlo = 0, whi = 0;
@@ -351,17 +507,23 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
     };
     // act-side issue state (the operand does not depend on the h tile)
     int as = 0, ad = 0;
-    size_t abase = 0;
-    bool acol = false;
+    size_t abase[NC];
+    bool acol[NC];
     auto enter_a = [&]() {
-        acol = col < g.cnt[ad];
-        abase = (size_t)(acol ? g.assign[ad][col] : 0) * F + k0 + lm.kq8;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            acol[c] = col + 16 * c < g.cnt[ad];
+            abase[c] = (size_t)(acol[c] ? g.assign[ad][col + 16 * c] : 0) * F + k0 + lm.kq8;
+        }
     };
     enter_a();
     auto issue_a = [&](int i) {
-        const bool on = as < n_valid && acol;
-        aa[i] = load16(p.act + abase + as * 64, on);
-        ab[i] = load16(p.act + abase + as * 64 + 32, on);
+        const bool on = as < n_valid;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            aa[i][c] = load16(p.act + abase[c] + as * 64, on && acol[c]);
+            ab[i][c] = load16(p.act + abase[c] + as * 64 + 32, on && acol[c]);
+        }
         if (++as == spt) {
             as = 0;
             if (++ad == D) ad = 0;
@@ -387,15 +549,19 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
     for (int i = 0; i < P; ++i) issue_a(i);
 
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    f32x4 acc1 = zero, acc2 = zero;
+    f32x4 acc1[NC], acc2[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc1[c] = acc2[c] = zero;
     int cs = 0, cd = 0, ct = blockIdx.x, par = 0;
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, hi[i], lo[i]),
-                                                           __builtin_bit_cast(bf16x8, aa[i]), acc1, 0, 0, 0);
-            acc2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pick(lm.upper, lo[i], hi[i]),
-                                                           __builtin_bit_cast(bf16x8, ab[i]), acc2, 0, 0, 0);
+            const bf16x8 a1 = pick(lm.upper, hi[i], lo[i]), a2 = pick(lm.upper, lo[i], hi[i]);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                acc1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, aa[i][c]), acc1[c], 0, 0, 0);
+                acc2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8, ab[i][c]), acc2[c], 0, 0, 0);
+            }
             if (q + P + i < total_q) {
                 issue_w(i);
                 issue_a(i);
@@ -403,26 +569,30 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
         }
         cs += P;
         if (cs == spt) {
-            sm.red[par][wave][0][lane] = fold_halves(acc1, acc2);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) sm.red[par][wave][0][c][lane] = fold_halves(acc1[c], acc2[c]);
             lds_barrier();
-            if (tid < 256) {
-                const int pl = tid & 63, r = tid >> 6;
-                const int c = pl & 15;
-                if (c < g.cnt[cd]) {
+            const int cnt = g.cnt[cd];
+            for (int item = tid; item < 256 * NC; item += kThreads) {
+                const int c = item >> 8, pl = item & 63, r = (item >> 6) & 3;
+                const int tok = (pl & 15) + 16 * c;
+                if (tok < cnt) {
                     float s = 0.f;
 #pragma unroll
-                    for (int w = 0; w < kWaves; ++w) s += sm.red[par][w][0][pl][r];
-                    const int a = g.assign[cd][c];
-                    sm.yacc[a / k][4 * (pl >> 4) + r] += sm.route.w[a] * s;
+                    for (int w = 0; w < kWaves; ++w) s += sm.red[par][w][0][c][pl][r];
+                    const int a = g.assign[cd][tok];
+                    sm.yacc[a / k][4 * (pl >> 4) + r] += sm.w[a] * s;
                 }
             }
-            acc1 = acc2 = zero;
+            if (Smem<NC>::kRedBufs == 1) lds_barrier();  // the single buffer is free again
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc1[c] = acc2[c] = zero;
             cs = 0;
-            par ^= 1;
+            par = (par + 1) % Smem<NC>::kRedBufs;
             if (++cd == D) {
                 lds_barrier();  // the tile's sums are complete
-                if (tid < p.T * 16) {
-                    const int t = tid >> 4, r = tid & 15;
+                for (int item = tid; item < p.T * 16; item += kThreads) {
+                    const int t = item >> 4, r = item & 15;
                     p.y[(size_t)t * H + ct * 16 + r] = to_bf16(sm.yacc[t][r]);
                     sm.yacc[t][r] = 0.f;
                 }
@@ -433,14 +603,16 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem& sm) {
     }
 }
 
-// The whole MoE layer of a decode-size call in one launch.  Every workgroup must be resident at
-// the same time (grid <= number of compute units, one 512-thread workgroup each).
-template <int P1, int P2, bool ROUTE>
+// The whole MoE layer of a decode-size call in one launch (NC = 1, ROUTE), or the expert FFN of a
+// call of up to 16 * NC tokens whose selections were made earlier.  Every workgroup must be
+// resident at the same time (grid <= number of compute units, one 512-thread workgroup each).
+template <int P1, int P2, bool ROUTE, int NC>
 __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
-    __shared__ Smem sm;
+    static_assert(!ROUTE || NC == 1, "in-kernel routing serves at most 16 tokens");
+    __shared__ Smem<NC> sm;
     const int tid = threadIdx.x;
     const int A = p.T * p.k;
-    if (tid < kMaxTok * 16) sm.yacc[tid >> 4][tid & 15] = 0.f;
+    for (int i = tid; i < 16 * NC * 16; i += kThreads) sm.yacc[i >> 4][i & 15] = 0.f;
     if (ROUTE) {
         // Every workgroup routes the call itself (identical arithmetic, identical result), which
         // costs a few microseconds of latency instead of a kernel boundary; workgroup 0 publishes.
@@ -449,7 +621,11 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
         if (publish && tid < p.E && p.accumulate) old_count = p.counts[tid];
         static_assert(sizeof(sm.red) >= kRoutePartFloats * sizeof(float), "routing borrows the reduction buffer");
         route_tokens_wg<uint16_t>(p.x, p.wg, p.bias, p.T, p.H, p.E, p.k, sm.route,
-                                  reinterpret_cast<float*>(&sm.red[0][0][0][0]));
+                                  reinterpret_cast<float*>(&sm.red[0][0][0][0][0]));
+        if (tid < A) {
+            sm.idx[tid] = sm.route.idx[tid];
+            sm.w[tid] = sm.route.w[tid];
+        }
         if (publish) {
             if (tid < A) {
                 p.idx_out[tid] = sm.route.idx[tid];
@@ -462,15 +638,16 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
             }
         }
     } else {
-        if (tid < A) {
-            sm.route.idx[tid] = p.idx_in[tid];
-            sm.route.w[tid] = p.w_in[tid];
+        for (int i = tid; i < A; i += kThreads) {
+            sm.idx[i] = p.idx_in[i];
+            sm.w[i] = p.w_in[i];
         }
-        __syncthreads();
     }
-    build_groups(sm.g, sm.route.idx, A, p.E);
-    gemm1_phase<P1>(p, sm);
-    gemm2_phase<P2>(p, sm);
+    __syncthreads();
+    build_groups<NC>(sm.g, sm.idx, A, p.E);
+    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm);
+    else gemm1_phase<P1, NC>(p, sm);
+    gemm2_phase<P2, NC>(p, sm);
 }
 
 std::atomic<uint32_t> g_epoch{0};
@@ -509,8 +686,13 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     p.F = s.ffn;
     const int max_tiles1 = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
     const int grid = min(min(compute_units(), kDecodeFlagInts), max(max_tiles1, s.hidden / 16));
-    if (route != nullptr) decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, true><<<grid, kThreads, 0, stream>>>(p);
-    else decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false><<<grid, kThreads, 0, stream>>>(p);
+    if (route != nullptr) {
+        decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, true, 1><<<grid, kThreads, 0, stream>>>(p);
+    } else if (tokens <= 16) {
+        decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 1><<<grid, kThreads, 0, stream>>>(p);
+    } else {
+        decode_layer_kernel<2, 4, false, 2><<<grid, kThreads, 0, stream>>>(p);
+    }
     stage_mark(stream, kStageFused);
     return hipGetLastError();
 }

@@ -271,7 +271,11 @@ struct Gemm {
         // wq * kFeatPerWave + 32 j.
         int trow[kTF], wrow[kWF];
 #pragma unroll
-        for (int i = 0; i < kTF; ++i) trow[i] = wt * (32 * kTF) + i * 32 + frow;
+        for (int i = 0; i < kTF; ++i) trow[i] = (i * WT + wt) * 32 + frow;
+        // Slot fragments (32 slots each) are dealt to the slot groups round-robin, so the valid slots of
+        // a ragged tile spread evenly over the wavefronts (and the SIMDs they sit on); fragments that lie
+        // entirely past the tile's last slot are skipped: n_tf = this wavefront's fragments with valid slots.
+        const int n_tf = __builtin_amdgcn_readfirstlane(min(kTF, max(0, (rows - wt * 32 + 32 * WT - 1) / (32 * WT))));
 #pragma unroll
         for (int j = 0; j < kWF; ++j)
             wrow[j] = (j / kFragsPerMat) * 128 * (NMAT - 1) + wq * kFeatPerWave + (j % kFragsPerMat) * 32 + frow;
@@ -293,7 +297,7 @@ struct Gemm {
             if (idx < kWF)
                 wf[buf][idx] = *reinterpret_cast<const bf16x8*>(
                     st + kTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
-            else
+            else if (idx - kWF < n_tf)
                 tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
                     st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
         };
@@ -305,7 +309,8 @@ struct Gemm {
             for (int m = 0; m < kM; ++m) {
                 if (decltype(mfma)::value) {
                     const int i = m / kWF, j = m % kWF;
-                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
+                    if (i < n_tf)
+                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
                 }
                 if (decltype(read)::value && m < kR) read_one(rstage, rks, rbuf, m);
                 if (m >= kM - kLoadsPerPart && dma) dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
@@ -402,7 +407,7 @@ struct Gemm {
             // [256 slots][128 features] bf16, 256-byte rows, unit v of row r at position v ^ (r & 15)
 #pragma unroll
             for (int i = 0; i < kTF; ++i) {
-                const int row = wt * (32 * kTF) + i * 32 + frow;
+                const int row = (i * WT + wt) * 32 + frow;
 #pragma unroll
                 for (int jf = 0; jf < kFragsPerMat; ++jf) {
 #pragma unroll
@@ -448,7 +453,7 @@ struct Gemm {
                 }
                 lds_barrier();
                 for (int lr = wave; lr < 32 * WT; lr += kWaves) {
-                    const int row = (lr >> 5) * (32 * kTF) + i * 32 + (lr & 31);  // slot in tile
+                    const int row = i * (32 * WT) + lr;  // slot in tile: fragment i * WT + lr / 32
                     const int n = n0 + lane * 4;
                     if (row < rows && n < N) {
                         const f32x4 v = *reinterpret_cast<const f32x4*>(lds + lr * 1024 + ((lane ^ (lr & 63)) << 4));

@@ -23,7 +23,7 @@ WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
     L.act = off;         off = align_up(off + A * (size_t)s.ffn * esz);
     L.out = off;         off = align_up(off + A * (size_t)s.hidden * sizeof(float));
     L.partial = off;
-    if (s.dtype == MOE_BF16 && tokens > kDecodeMaxTokens) off = align_up(off + kGemmScratchBytes);
+    if (s.dtype == MOE_BF16 && tokens > kStreamMaxTokens) off = align_up(off + kGemmScratchBytes);
     L.total = off;
     return L;
 }
@@ -111,7 +111,10 @@ int check_optional(const void* const (&ptrs)[N]) {
 
 int dev(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE; }
 
+// bf16 calls of at most kDecodeMaxTokens tokens run as one kernel (routing included); up to
+// kStreamMaxTokens the expert FFN still uses that kernel's weight-streaming phases.
 bool decode_path(const moe_shape_t& s, int tokens) { return s.dtype == MOE_BF16 && tokens <= kDecodeMaxTokens; }
+bool stream_path(const moe_shape_t& s, int tokens) { return s.dtype == MOE_BF16 && tokens <= kStreamMaxTokens; }
 
 struct Ws {
     int32_t *hist, *hist_next, *offs, *row_of_slot, *slot_of, *sync;
@@ -169,7 +172,7 @@ hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* 
 
 hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_t* idx, const float* w,
                    const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream) {
-    if (decode_path(s, tokens))
+    if (stream_path(s, tokens))
         return launch_decode_layer(s, tokens, x, nullptr, idx, w, w1, w3, w2, y, ws.act, ws.dec_flags, stream);
     if (s.dtype == MOE_F32)
         return launch_ffn_f32(s, tokens, static_cast<const float*>(x), w, static_cast<const float*>(w1),
@@ -276,7 +279,7 @@ int moe_expert_ffn(const moe_shape_t* shape, int32_t tokens, const void* x, cons
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Ws ws = carve(workspace, L);
     stage_call_begin(stream);
-    if (!decode_path(*shape, tokens)) {
+    if (!stream_path(*shape, tokens)) {
         hipError_t e = launch_hist_from_idx(*shape, tokens, topk_idx, ws.hist, stream);
         if (e != hipSuccess) return MOE_ERR_DEVICE;
         e = launch_finalize(*shape, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, ws.sync, stream);
@@ -320,7 +323,7 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
     }
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;
-    hipError_t e = run_route(*shape, tokens, x, g, n_gates, counts, accumulate, nullptr, !decode_path(*shape, tokens), ws,
+    hipError_t e = run_route(*shape, tokens, x, g, n_gates, counts, accumulate, nullptr, !stream_path(*shape, tokens), ws,
                              stream);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));

@@ -16,6 +16,11 @@ constexpr int kRouteTokensPerBlock = 16;
 // weight-streaming kernel that routes, groups tokens per expert on the fly
 // (no permutation in the workspace) and runs both expert GEMMs.
 constexpr int kDecodeMaxTokens = 16;
+// bf16 calls with at most this many tokens still stream the weights with that kernel's two GEMM
+// phases (routing, counts and prediction then come from the prefill-size routing kernels): below
+// this size the layer is bound by reading each selected expert once and the streaming kernel beats
+// the 256-row MFMA tiles (measured: 617 vs 737 us at 32 tokens; at 64 tokens it loses, 863 vs 782 us).
+constexpr int kStreamMaxTokens = 32;
 
 // Rows (tokens) per M-tile of the grouped GEMMs; an M-tile never spans two experts.
 constexpr int kTileTokensF32 = 64;

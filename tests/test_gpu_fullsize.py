@@ -52,8 +52,9 @@ def test_mixtral_decode(oracle, mixtral, T):
     _layer(oracle, mixtral, MIXTRAL, T, T, f"mixtral decode T={T}")
 
 
-def test_mixtral_32_tokens(oracle, mixtral):
-    _layer(oracle, mixtral, MIXTRAL, 32, 32, "mixtral T=32")
+@pytest.mark.parametrize("T", [32, 64, 100])
+def test_mixtral_mid_sizes(oracle, mixtral, T):
+    _layer(oracle, mixtral, MIXTRAL, T, 32, f"mixtral T={T}")
 
 
 @pytest.mark.parametrize("T", [512, 4096])

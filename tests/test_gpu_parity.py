@@ -37,6 +37,7 @@ def test_config0_tiny_fp32_layer(oracle):
     (90, 192, 128, 32, 3),     # two 16-expert blocks in the router
     (40, 8192, 128, 8, 2),     # hidden dimension longer than one register chunk of the router
     (60, 128, 128, 12, 3),     # expert count that is not a power of two
+    (32, 256, 512, 8, 2), (33, 256, 320, 16, 2), (64, 256, 512, 8, 2), (65, 256, 512, 8, 2),   # weight-streaming sizes and the first size past them
 ])
 def test_bf16_prefill_path(oracle, T, H, F, E, k):
     d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
@@ -63,7 +64,7 @@ def test_fp32_path(oracle, T, H, F, E, k):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("T", [9, 150])
+@pytest.mark.parametrize("T", [9, 30, 64, 150])
 def test_layer_equals_route_predict_ffn_bitwise(dtype, T):
     H, F, E, k = 256, 512, 8, 2
     d, shape, out, res = _run(T, H, F, E, k, dtype)
@@ -87,7 +88,7 @@ def test_layer_equals_route_predict_ffn_bitwise(dtype, T):
     assert torch.all((pw.sum(1) - 1).abs() < 1e-5)
 
 
-@pytest.mark.parametrize("T", [8, 260])
+@pytest.mark.parametrize("T", [8, 48, 260])
 def test_repeatable_and_independent_of_workspace_contents(T):
     H, F, E, k, dtype = 256, 512, 8, 2, torch.bfloat16
     d, shape, out, res = _run(T, H, F, E, k, dtype)
@@ -134,7 +135,7 @@ def test_counts_accumulate_over_calls_and_zero_tokens(oracle):
 def test_all_tokens_to_one_expert_equals_its_dense_ffn(oracle):
     # the degenerate grouping: one expert owns every slot (k = 1, +50 bias), both paths
     H, F, E, dtype = 256, 512, 8, torch.bfloat16
-    for T in (12, 16, 17, 32, 300):
+    for T in (12, 16, 17, 32, 33, 64, 65, 300):
         d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, zipf_s=None, with_next=False)
         d["bias"] = torch.zeros(E, dtype=torch.float32, device=DEV)
         d["bias"][5] = 50.0
