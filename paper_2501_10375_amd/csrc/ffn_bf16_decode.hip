@@ -34,8 +34,9 @@
 //     window (software pipeline unrolled P times) that runs across tile
 //     boundaries, and the barrier at a tile's end waits for LDS only, so the
 //     stream never drains;
-//   * the 8 wavefronts of a workgroup split K, and their partial 16 x 16 tiles
-//     are summed through LDS in a fixed order (deterministic);
+//   * the 8 wavefronts of a workgroup split K (interleaved 64-element steps),
+//     and their partial 16 x 16 tiles are summed through LDS in a fixed order
+//     (deterministic);
 //   * between the two GEMMs every workgroup needs the whole intermediate
 //     vector: a grid-wide barrier made of one arrival flag per workgroup, each
 //     set to a per-launch epoch, so the flags never need clearing and no
@@ -68,14 +69,50 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // Pipeline depths (64-element K steps of loads in flight per wavefront) of the two GEMM phases.
 #ifndef MOE_DEC_P1
-#define MOE_DEC_P1 4
+#define MOE_DEC_P1 2
 #endif
 #ifndef MOE_DEC_P2
-#define MOE_DEC_P2 8
+#define MOE_DEC_P2 4
 #endif
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
+// How the wavefronts of a workgroup split K (64-element steps): interleaved (wavefront w takes steps
+// w, w + 8, ...; at any moment the workgroup reads one contiguous 1 KB piece of each weight row) or
+// in contiguous runs.
+#ifndef MOE_DEC_KINTERLEAVE
+#define MOE_DEC_KINTERLEAVE 1
+#endif
+// Optional timestamps per workgroup for tuning (compiled out unless MOE_DEC_TRACE is defined).
+#ifdef MOE_DEC_TRACE
+__device__ unsigned long long g_dec_trace[512][8];
+#define DEC_TRACE(slot) do { if (threadIdx.x == 0) g_dec_trace[blockIdx.x][slot] = wall_clock64(); } while (0)
+#else
+#define DEC_TRACE(slot) do { } while (0)
+#endif
+// Phase-1 tiles are dealt to the workgroups round-robin (1) or in contiguous runs (0).
+#ifndef MOE_DEC_TILE_RR
+#define MOE_DEC_TILE_RR 1
+#endif
+struct KSplit {
+    int n_valid;     // steps of this wavefront
+    int stride;      // elements between its consecutive steps
+    size_t k0;       // element offset of its first step
+    int per;         // steps of the busiest wavefront
+    __device__ KSplit(int k_steps, int wave) {
+        per = (k_steps + kWaves - 1) / kWaves;
+        if (MOE_DEC_KINTERLEAVE) {
+            n_valid = wave < k_steps ? (k_steps - wave + kWaves - 1) / kWaves : 0;
+            stride = 64 * kWaves;
+            k0 = (size_t)wave * 64;
+        } else {
+            const int s_begin = wave * per;
+            n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
+            stride = 64;
+            k0 = (size_t)s_begin * 64;
+        }
+    }
+};
 // An expert's tokens are the columns of 16x16x32 MFMAs: NC column groups of 16 serve calls of up to
 // 16 * NC tokens (a token selects an expert at most once, so no expert sees more tokens than the call has).
 static_assert(kStreamMaxTokens == 32, "column groups are instantiated for 16 and 32 tokens");
@@ -217,11 +254,9 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
     if (t0 >= t1) return;
 
     // K split: 64-element steps dealt to the wavefronts in contiguous runs.
-    const int k_steps = H / 64;
-    const int per = (k_steps + kWaves - 1) / kWaves;
-    const int s_begin = wave * per;
-    const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
-    const int spt = (per + P - 1) / P * P;  // steps per tile, padded to the pipeline depth
+    const KSplit ks(H / 64, wave);
+    const int n_valid = ks.n_valid, kstride = ks.stride;
+    const int spt = (ks.per + P - 1) / P * P;  // steps per tile, padded to the pipeline depth
     const long total_q = (long)(t1 - t0) * spt;
 
     u32x4 lo1[P], hi1[P], lo3[P], hi3[P], xa[P][NC], xb[P][NC];
@@ -233,7 +268,7 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
         const int d = itile / tiles_per_expert;
         const int f0 = (itile - d * tiles_per_expert) * 16;
         const size_t row0 = (size_t)g.expert[d] * F + f0;
-        const size_t k0 = (size_t)s_begin * 64;
+        const size_t k0 = ks.k0;
         wlo = (row0 + lm.row_lo) * H + k0 + lm.k_lo;
         whi = (row0 + lm.row_hi) * H + k0 + lm.k_hi;
 #pragma unroll
@@ -245,14 +280,14 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
     enter_tile();
     auto issue = [&](int i) {
         const bool on = is < n_valid;
-        lo1[i] = load16(p.w1 + wlo + is * 64, on);
-        hi1[i] = load16(p.w1 + whi + is * 64, on);
-        lo3[i] = load16(p.w3 + wlo + is * 64, on);
-        hi3[i] = load16(p.w3 + whi + is * 64, on);
+        lo1[i] = load16(p.w1 + wlo + is * kstride, on);
+        hi1[i] = load16(p.w1 + whi + is * kstride, on);
+        lo3[i] = load16(p.w3 + wlo + is * kstride, on);
+        hi3[i] = load16(p.w3 + whi + is * kstride, on);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            xa[i][c] = load16(p.x + xbase[c] + is * 64, on && xcol[c]);
-            xb[i][c] = load16(p.x + xbase[c] + is * 64 + 32, on && xcol[c]);
+            xa[i][c] = load16(p.x + xbase[c] + is * kstride, on && xcol[c]);
+            xb[i][c] = load16(p.x + xbase[c] + is * kstride + 32, on && xcol[c]);
         }
         if (++is == spt) {
             is = 0;
@@ -332,6 +367,13 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
 // operand of an expert is the same for every feature tile, so its fragments are loaded once per
 // expert and stay in registers; only weights stream.  A tile is exactly kXSteps steps (statically
 // indexed fragments), steps past the slice multiply zeros.
+//
+// Tiles are dealt to the workgroups round-robin (tile b + n * grid), so every XCD reads from every
+// part of the matrices.  (How fast a workgroup streams depends on where its data lives relative to
+// its XCD, by several percent and differently in every call.  Handing the last rounds out on demand
+// from ticket counters was measured and lost: a unit has to be claimed a unit or two ahead to keep
+// the load pipeline full, which is as coarse as the imbalance it is meant to remove, and the
+// counters cost more than they saved.)
 constexpr int kXSteps = 8;
 template <int P, int NC>
 __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
@@ -344,21 +386,24 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
 
     const int tiles_per_expert = F / 16;
     const int total_tiles = g.n_active * tiles_per_expert;
+    // This workgroup's tiles, numbered n = 0 .. n_mine - 1 in ascending tile order.
     const int tiles_per_wg = (total_tiles + gridDim.x - 1) / gridDim.x;
     const int t0 = blockIdx.x * tiles_per_wg;
-    const int t1 = min(total_tiles, t0 + tiles_per_wg);
+    const int n_mine = MOE_DEC_TILE_RR
+                           ? ((int)blockIdx.x < total_tiles ? (total_tiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0)
+                           : max(0, min(total_tiles, t0 + tiles_per_wg) - t0);
+    auto tile_id = [&](int n) { return MOE_DEC_TILE_RR ? (int)blockIdx.x + n * (int)gridDim.x : t0 + n; };
 
-    const int k_steps = H / 64;
-    const int per = (k_steps + kWaves - 1) / kWaves;  // <= kXSteps
-    const int s_begin = wave * per;
-    const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
-    const size_t k0 = (size_t)s_begin * 64;
+    const KSplit ks(H / 64, wave);  // ks.per <= kXSteps
+    const int n_valid = ks.n_valid, kstride = ks.stride;
+    const size_t k0 = ks.k0;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     int par = 0;
 
-    for (int seg0 = t0; seg0 < t1;) {
-        const int d = seg0 / tiles_per_expert;
-        const int seg1 = min(t1, (d + 1) * tiles_per_expert);
+    for (int seg0 = 0; seg0 < n_mine;) {  // a segment = this workgroup's tiles of one expert
+        const int d = tile_id(seg0) / tiles_per_expert;
+        int seg1 = seg0 + 1;
+        while (seg1 < n_mine && tile_id(seg1) / tiles_per_expert == d) ++seg1;
         const int cnt = g.cnt[d];
         const size_t erow0 = (size_t)g.expert[d] * F;
 
@@ -370,26 +415,30 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
             const uint16_t* xp = p.x + (size_t)(on ? g.assign[d][col + 16 * c] / k : 0) * H + k0 + lm.kq8;
 #pragma unroll
             for (int s = 0; s < kXSteps; ++s) {
-                xr[s][c][0] = load16(xp + s * 64, on && s < n_valid);
-                xr[s][c][1] = load16(xp + s * 64 + 32, on && s < n_valid);
+                xr[s][c][0] = load16(xp + s * kstride, on && s < n_valid);
+                xr[s][c][1] = load16(xp + s * kstride + 32, on && s < n_valid);
             }
         }
 
         // weight stream over the tiles [seg0, seg1), P steps ahead
         u32x4 lo1[P], hi1[P], lo3[P], hi3[P];
         int is = 0, itile = seg0;
+        size_t wlo = 0, whi = 0;
+        auto enter_tile = [&]() {
+            const int f0 = (tile_id(itile) - d * tiles_per_expert) * 16;
+            wlo = (erow0 + f0 + lm.row_lo) * H + k0 + lm.k_lo;
+            whi = (erow0 + f0 + lm.row_hi) * H + k0 + lm.k_hi;
+        };
+        enter_tile();
         auto issue = [&](int i) {
-            const int f0 = (itile - d * tiles_per_expert) * 16;
-            const size_t wlo = (erow0 + f0 + lm.row_lo) * H + k0 + lm.k_lo + is * 64;
-            const size_t whi = (erow0 + f0 + lm.row_hi) * H + k0 + lm.k_hi + is * 64;
             const bool on = is < n_valid && itile < seg1;
-            lo1[i] = load16(p.w1 + wlo, on);
-            hi1[i] = load16(p.w1 + whi, on);
-            lo3[i] = load16(p.w3 + wlo, on);
-            hi3[i] = load16(p.w3 + whi, on);
+            lo1[i] = load16(p.w1 + wlo + is * kstride, on);
+            hi1[i] = load16(p.w1 + whi + is * kstride, on);
+            lo3[i] = load16(p.w3 + wlo + is * kstride, on);
+            hi3[i] = load16(p.w3 + whi + is * kstride, on);
             if (++is == kXSteps) {
                 is = 0;
-                ++itile;
+                if (++itile < seg1) enter_tile();
             }
         };
 #pragma unroll
@@ -401,8 +450,7 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
             for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
 #pragma unroll
             for (int s = 0; s < kXSteps; ++s) {
-                constexpr int kP = P;
-                const int i = s % kP;
+                const int i = s % P;
                 const bf16x8 a1 = pick(lm.upper, hi1[i], lo1[i]), a2 = pick(lm.upper, lo1[i], hi1[i]);
                 const bf16x8 a3 = pick(lm.upper, hi3[i], lo3[i]), a4 = pick(lm.upper, lo3[i], hi3[i]);
 #pragma unroll
@@ -424,7 +472,7 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
                 sm.red[par][wave][1][c][lane] = fold_halves(u1[c], u2[c]);
             }
             lds_barrier();
-            const int f0 = (ctile - d * tiles_per_expert) * 16;
+            const int f0 = (tile_id(ctile) - d * tiles_per_expert) * 16;
             for (int item = tid; item < 128 * NC; item += kThreads) {
                 const int c = item >> 7, pl = item & 63, rp = (item >> 6) & 1;
                 const int tok = (pl & 15) + 16 * c;
@@ -467,19 +515,18 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
 
     const int h_tiles = H / 16;
     const int my_tiles = blockIdx.x < h_tiles ? (h_tiles - 1 - blockIdx.x) / n_wgs + 1 : 0;
-    const int k_steps = F / 64;
-    const int per = (k_steps + kWaves - 1) / kWaves;
-    const int s_begin = wave * per;
-    const int n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
-    const int spt = (per + P - 1) / P * P;
+    const KSplit ks(F / 64, wave);
+    const int n_valid = ks.n_valid, kstride = ks.stride;
+    const int spt = (ks.per + P - 1) / P * P;
     const int D = g.n_active;
     const long total_q = (long)my_tiles * D * spt;
-    const size_t k0 = (size_t)s_begin * 64;
+    const size_t k0 = ks.k0;
 
     // ---- everything this workgroup stored to `act` has left the CU; announce it
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) __hip_atomic_store(&p.flags[blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    DEC_TRACE(3);
     if (total_q == 0) return;
 
     u32x4 lo[P], hi[P], aa[P][NC], ab[P][NC];
@@ -494,8 +541,8 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     enter_w();
     auto issue_w = [&](int i) {
         const bool on = ws < n_valid;
-        lo[i] = load16(p.w2 + wlo + ws * 64, on);
-        hi[i] = load16(p.w2 + whi + ws * 64, on);
+        lo[i] = load16(p.w2 + wlo + ws * kstride, on);
+        hi[i] = load16(p.w2 + whi + ws * kstride, on);
         if (++ws == spt) {
             ws = 0;
             if (++wd == D) {
@@ -521,8 +568,8 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
         const bool on = as < n_valid;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            aa[i][c] = load16(p.act + abase[c] + as * 64, on && acol[c]);
-            ab[i][c] = load16(p.act + abase[c] + as * 64 + 32, on && acol[c]);
+            aa[i][c] = load16(p.act + abase[c] + as * kstride, on && acol[c]);
+            ab[i][c] = load16(p.act + abase[c] + as * kstride + 32, on && acol[c]);
         }
         if (++as == spt) {
             as = 0;
@@ -545,6 +592,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
         }
     }
     __syncthreads();
+    DEC_TRACE(4);
 #pragma unroll
     for (int i = 0; i < P; ++i) issue_a(i);
 
@@ -612,6 +660,7 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     __shared__ Smem<NC> sm;
     const int tid = threadIdx.x;
     const int A = p.T * p.k;
+    DEC_TRACE(0);
     for (int i = tid; i < 16 * NC * 16; i += kThreads) sm.yacc[i >> 4][i & 15] = 0.f;
     if (ROUTE) {
         // Every workgroup routes the call itself (identical arithmetic, identical result), which
@@ -644,10 +693,13 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
         }
     }
     __syncthreads();
+    DEC_TRACE(1);
     build_groups<NC>(sm.g, sm.idx, A, p.E);
+    DEC_TRACE(2);
     if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm);
     else gemm1_phase<P1, NC>(p, sm);
     gemm2_phase<P2, NC>(p, sm);
+    DEC_TRACE(5);
 }
 
 std::atomic<uint32_t> g_epoch{0};
