@@ -167,11 +167,10 @@ struct Gemm {
     // wa, wb: [E, N, K]; dst: gemm1 -> bf16 [A, N]; gemm2 -> fp32 [A, N].
     //
     // Persistent schedule: the grid is one workgroup per CU.  Workgroup b belongs to XCD b % 8 (the
-    // hardware deals workgroups round-robin to the XCDs) and is its member b / 8.  Each XCD owns one
-    // contiguous eighth of the tile list and works through it in rounds of `members` consecutive
-    // tiles, one per member.  Before each new round the members meet (xcd_rendezvous), so they walk
-    // K in step and every operand line is pulled into the XCD's L2 once per round instead of once
-    // per workgroup.
+    // hardware deals workgroups round-robin to the XCDs) and is its member b / 8.  An XCD works
+    // through the tile list in rounds of `members` consecutive tiles, one per member.  Before each
+    // new round the members meet (xcd_rendezvous), so they walk K in step and every operand line is
+    // pulled into the XCD's L2 once per round instead of once per workgroup.
     //
     // The last round usually has fewer tiles than members (`rem`).  Each of its tiles is then split
     // along K into `parts` = min(kMaxSplit, members / rem) pieces computed by different members.
@@ -189,10 +188,16 @@ struct Gemm {
         const int xcd = blockIdx.x % kXcds, member = blockIdx.x / kXcds;
         const int members = min((int)gridDim.x / kXcds, kMaxWgsPerXcd);
         if (member >= members) return;
-        const int chunk = (total + kXcds - 1) / kXcds;
-        const int first = xcd * chunk, last = min(total, first + chunk);
-        const int len = max(last - first, 0);
-        const int full_rounds = len / members, rem = len - full_rounds * members;
+        // Full rounds: round r of XCD x is tiles [(r * 8 + x) * members, +members) of the list, so the
+        // XCDs take turns along the list and each sees the same mix of heavy tiles (hot experts, full
+        // slot tiles) and light ones (cold experts, whose rounds are bound by streaming their weights).
+        // The tiles left over after the last full round of all XCDs are split evenly between the XCDs.
+        const int per_super_round = kXcds * members;
+        const int full_rounds = total / per_super_round;
+        const int left = total - full_rounds * per_super_round;
+        const int chunk = (left + kXcds - 1) / kXcds;
+        const int rem = max(0, min(left, (xcd + 1) * chunk) - xcd * chunk);
+        const int rem_first = full_rounds * per_super_round + xcd * chunk;
         const int parts = rem > 0 ? max(1, min(min(kMaxSplit, members / rem), KT / STAGES)) : 1;
         const int rounds = full_rounds + (rem > 0 ? 1 : 0);
         for (int r = 0; r < rounds; ++r) {
@@ -201,8 +206,9 @@ struct Gemm {
             const int p = split ? parts : 1;
             if (split && member >= rem * p) break;
             const int t = member / p, part = member - t * p;
+            const int tile_index = split ? rem_first + t : (r * kXcds + xcd) * members + t;
             int e, slot0, rows, ft;
-            tile_of(offs, E, n_ftiles, first + r * members + t, e, slot0, rows, ft);
+            tile_of(offs, E, n_ftiles, tile_index, e, slot0, rows, ft);
             const int kt0 = (int)((long)KT * part / p), kt1 = (int)((long)KT * (part + 1) / p);
             tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft, kt0, kt1, p, part,
                  scratch + ((size_t)xcd * kMaxWgsPerXcd + (size_t)t * p) * kPartialFloats,
