@@ -103,6 +103,18 @@ def run_stack(args):
     resident_before = (P * cache.int()).sum().item() / P.sum().item()
     _, n_swaps = policy.daop_plan_swaps(P, cache)
     resident_after = (P * cache.int()).sum().item() / P.sum().item()
+    # what DAOP's decode approximation (predicted experts, stale inputs for experts outside the cache) does to the
+    # output of the synthetic stack, by expert cache ratio: cache from the decode counts, then Algorithm 1 on the
+    # prefill counts
+    hq = torch.cat(hs[:8], dim=0)
+    exact_h = st.forward(hq, st.new_counts())["h"].clone()
+    precalc = []
+    for ecr in (0.25, 0.46875, 0.75, 1.0):
+        c = policy.daop_memory_init(D, int(round(ecr * L * E)))
+        policy.daop_plan_swaps(P, c)
+        r = stack.forward_precalc(st, hq, c, first_predicted_layer=5)
+        precalc.append({"expert_cache_ratio": ecr, "stale_selections": r["stale_selections"],
+                        "rel_err_final_hidden": ((r["h"] - exact_h).norm() / exact_h.norm()).item()})
     dec_bytes = steps * L * (2 * 3.0 * H * F * 2)   # two experts per token and layer
     print(json.dumps({
         "metric": "moe_stack_decode_tokens_per_s", "value": steps / (d_gpu_ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
@@ -123,6 +135,7 @@ def run_stack(args):
         "algorithm1": {"cache_slots": int(cache.sum().item()), "swaps": int(n_swaps.sum().item()),
                        "prefill_tokens_on_resident_experts_before": resident_before,
                        "prefill_tokens_on_resident_experts_after": resident_after},
+        "precalculation_error_vs_cache_ratio": precalc,
         "prefill_counts_first_layers": P[:2].cpu().tolist(),
     }))
 

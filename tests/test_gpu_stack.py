@@ -72,3 +72,41 @@ def test_small_stack_teacher_forced_parity(oracle):
     covered_before = (P * before.int()).sum().item()
     covered_after = (P * cache.int()).sum().item()
     assert covered_after >= covered_before   # more prefill tokens hit GPU-resident experts after the swaps
+
+
+def test_precalculation_variant(oracle):
+    """DAOP's decode approximation on a small stack: exact when no layer is predicted; per layer the
+    mix of fresh and stale expert inputs matches the oracle evaluated the same way; the output
+    error against the exact stack shrinks as the cache grows."""
+    L, H, F, E, k, T = 6, 256, 512, 8, 2, 12
+    st = stack.MoeStack(L, H, F, E, k, torch.bfloat16, DEV, zipf_s=1.2, max_tokens=T)
+    h0 = synth.normal((T, H), 77, synth.TID_X, 1.0, torch.float32, DEV)
+    exact = st.forward(h0, st.new_counts())["h"].clone()
+
+    none = torch.zeros((L, E), dtype=torch.uint8, device=DEV)
+    same = stack.forward_precalc(st, h0, none, first_predicted_layer=L)
+    assert same["stale_selections"] == 0 and torch.equal(same["h"], exact)
+
+    errs = []
+    for slots in (0, L * E // 4, L * E // 2, L * E):
+        cache = policy.daop_memory_init(torch.ones((L, E), dtype=torch.int32, device=DEV).cumsum(1).int().contiguous(), slots)
+        r = stack.forward_precalc(st, h0, cache, first_predicted_layer=2, keep_layers=True)
+        torch.cuda.synchronize()
+        errs.append(((r["h"] - exact).norm() / exact.norm()).item())
+        if slots == L * E:
+            assert r["stale_selections"] == 0
+        # one predicted layer against the oracle: fresh experts on u_l, stale ones on u_{l-1}
+        l = 3
+        u_prev, u, idx, w, stale, out = r["layers"][l]
+        d = st.layers[l]
+        hd = host(dict(w1=d["w1"], w3=d["w3"], w2=d["w2"], u=u, u_prev=u_prev))
+        idx_h, w_h, st_h = idx.cpu().numpy(), w.cpu().numpy().astype(np.float64), stale.cpu().numpy()
+        ref = oracle.expert_ffn(hd["u"], idx_h, np.where(st_h, 0.0, w_h), hd["w1"], hd["w3"], hd["w2"]) \
+            + oracle.expert_ffn(hd["u_prev"], idx_h, np.where(st_h, w_h, 0.0), hd["w1"], hd["w3"], hd["w2"])
+        got = out.double().cpu().numpy()
+        scale = max(np.abs(ref).max(), 1e-6)
+        assert np.abs(got - ref).max() / scale < 3e-2
+        # the cache decides which selections are stale
+        assert np.array_equal(st_h, cache[l].cpu().numpy()[idx_h] == 0)
+    print("relative error of the final hidden state vs cache slots:", errs)
+    assert errs[-1] <= errs[0] + 1e-6 and errs[0] > 0
