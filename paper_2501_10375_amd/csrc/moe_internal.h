@@ -85,7 +85,8 @@ constexpr int kGemmSyncInts = 8 + 8 * 32;
 constexpr int kSyncInts = 2 * kGemmSyncInts;  // gemm1 and gemm2
 constexpr size_t kGemmScratchBytes = (size_t)8 * 32 * 256 * 256 * sizeof(float);
 // `sync` (may be null) is a block of kSyncInts counters that is cleared for the GEMMs that follow.
-hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
+// For long calls the histograms in `hist` are replaced by their per-block prefixes.
+hipError_t launch_finalize(const moe_shape_t& s, int tokens, int32_t* hist, const int32_t* idx,
                            int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
                            int32_t* slot_of, int32_t* sync, hipStream_t stream);
 

@@ -101,6 +101,79 @@ __global__ __launch_bounds__(256) void finalize_kernel(const int32_t* __restrict
     }
 }
 
+// ---- long calls: the fused kernel above sweeps all block histograms in every workgroup, which is
+// quadratic in the number of blocks.  Beyond kFusedBlocks blocks one workgroup turns the histograms
+// into per-block exclusive prefixes in place (and writes counts / offs), then one workgroup per
+// block ranks its selections from its own row.
+constexpr int kFusedBlocks = 1024;
+
+// 1024 threads = 16 block ranges x 64 expert lanes.
+__global__ __launch_bounds__(1024) void scan_blocks_kernel(int32_t* __restrict__ hist, int n_blocks, int E,
+                                                           int32_t* __restrict__ counts, int accumulate,
+                                                           int32_t* __restrict__ offs, int32_t* __restrict__ sync) {
+    __shared__ int part[16][64];
+    __shared__ int total[64];
+    const int tid = threadIdx.x, e = tid & 63, g = tid >> 6;
+    const int per = (n_blocks + 15) / 16;
+    const int b0 = g * per, b1 = min(n_blocks, b0 + per);
+    int sum = 0;
+    if (e < E)
+        for (int b = b0; b < b1; ++b) sum += hist[(size_t)b * E + e];
+    part[g][e] = sum;
+    __syncthreads();
+    if (g == 0) {
+        int run = 0;
+        for (int i = 0; i < 16; ++i) {
+            const int v = part[i][e];
+            part[i][e] = run;
+            run += v;
+        }
+        total[e] = run;
+    }
+    __syncthreads();
+    if (e < E) {
+        int run = part[g][e];
+        for (int b = b0; b < b1; ++b) {
+            const int v = hist[(size_t)b * E + e];
+            hist[(size_t)b * E + e] = run;
+            run += v;
+        }
+    }
+    if (tid == 0 && offs != nullptr) {
+        int run = 0;
+        for (int i = 0; i < E; ++i) {
+            offs[i] = run;
+            run += total[i];
+        }
+        offs[E] = run;
+    }
+    if (tid < E && counts != nullptr) counts[tid] = (accumulate ? counts[tid] : 0) + total[tid];
+    if (sync != nullptr)
+        for (int i = tid; i < kSyncInts; i += 1024) sync[i] = 0;
+}
+
+// prefix: the histograms after scan_blocks_kernel; offs from the same kernel.
+__global__ __launch_bounds__(256) void rank_kernel(const int32_t* __restrict__ prefix, const int32_t* __restrict__ offs,
+                                                   int E, int k, int tokens, const int32_t* __restrict__ idx,
+                                                   int32_t* __restrict__ row_of_slot, int32_t* __restrict__ slot_of) {
+    __shared__ int base[64];
+    __shared__ int local_e[kRouteTokensPerBlock * 8];
+    const int tid = threadIdx.x, blk = blockIdx.x;
+    if (tid < E) base[tid] = offs[tid] + prefix[(size_t)blk * E + tid];
+    const int a0 = blk * kRouteTokensPerBlock * k;
+    const int n_local = min(tokens * k, a0 + kRouteTokensPerBlock * k) - a0;
+    if (tid < n_local) local_e[tid] = min(max(idx[a0 + tid], 0), E - 1);
+    __syncthreads();
+    if (tid < n_local) {
+        const int e = local_e[tid];
+        int rank = 0;
+        for (int i = 0; i < tid; ++i) rank += (local_e[i] == e);
+        const int slot = base[e] + rank;
+        slot_of[a0 + tid] = slot;
+        row_of_slot[slot] = a0 + tid;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t* idx, int32_t* hist,
@@ -110,10 +183,15 @@ hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t*
     return hipGetLastError();
 }
 
-hipError_t launch_finalize(const moe_shape_t& s, int tokens, const int32_t* hist, const int32_t* idx,
+hipError_t launch_finalize(const moe_shape_t& s, int tokens, int32_t* hist, const int32_t* idx,
                            int32_t* counts, int accumulate, int32_t* offs, int32_t* row_of_slot,
                            int32_t* slot_of, int32_t* sync, hipStream_t stream) {
     const int nb = route_blocks(tokens);
+    if (row_of_slot != nullptr && nb > kFusedBlocks) {
+        scan_blocks_kernel<<<1, 1024, 0, stream>>>(hist, nb, s.n_experts, counts, accumulate, offs, sync);
+        rank_kernel<<<nb, 256, 0, stream>>>(hist, offs, s.n_experts, s.top_k, tokens, idx, row_of_slot, slot_of);
+        return hipGetLastError();
+    }
     const int grid = (row_of_slot != nullptr && nb > 0) ? nb : 1;
     finalize_kernel<<<grid, 256, 0, stream>>>(hist, nb, s.n_experts, s.top_k, tokens, idx, counts, accumulate,
                                               offs, row_of_slot, slot_of, sync);

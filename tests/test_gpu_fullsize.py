@@ -89,3 +89,25 @@ def test_mixtral_decode_sequence_on_one_workspace(mixtral, T):
         torch.cuda.synchronize()
         assert torch.equal(idx, ref["idx"]), f"step {step}"
         assert torch.equal(y.view(torch.int16), ref["y"].view(torch.int16)), f"step {step}"
+
+
+@pytest.mark.parametrize("T,dtype", [(20000, torch.bfloat16), (20000, torch.float32), (1 << 20, torch.bfloat16)])
+def test_long_calls_up_to_the_token_limit(oracle, T, dtype):
+    """More than 1024 routing blocks take the two-kernel counts/permutation path; 2^20 tokens is the
+    documented maximum.  Narrow layers keep the oracle's share in seconds."""
+    H, F, E, k = 64, 64, 8, 2
+    d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, seed=5, zipf_s=1.2)
+    shape = moe.make_shape(H, F, E, k, dtype)
+    out = moe.LayerOutputs(shape, T, dtype, DEV)
+    res = moe.run_layer(shape, d, out)
+    torch.cuda.synchronize()
+    assert int(res["counts"].sum().item()) == T * k
+    tokens = np.unique(np.linspace(0, T - 1, 48).astype(int))
+    r = check_layer(oracle, d, shape, res, dtype, tokens=tokens, label=f"long call T={T}")
+    print(r, flush=True)
+    assert r["excluded"] <= 0.01 * T
+    # the permutation is a bijection between assignments and slots, grouped by expert in token order
+    idx = res["idx"].flatten().long()
+    order = torch.argsort(idx, stable=True)
+    assert torch.equal(torch.bincount(idx, minlength=E).int(), res["counts"])
+    del order
