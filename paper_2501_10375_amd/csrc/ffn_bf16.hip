@@ -16,8 +16,14 @@ namespace moe {
 namespace {
 
 // Pipeline shape of the two GEMMs: K step and number of LDS stages (STAGES * 512 rows * BK * 2 bytes of LDS).
-constexpr int kBK = 32;
-constexpr int kStages = 4;
+#ifndef MOE_GEMM_BK
+#define MOE_GEMM_BK 32
+#endif
+#ifndef MOE_GEMM_STAGES
+#define MOE_GEMM_STAGES 4
+#endif
+constexpr int kBK = MOE_GEMM_BK;
+constexpr int kStages = MOE_GEMM_STAGES;
 constexpr int kWT = 2, kWW = 4;  // wavefront grid: slot groups x weight-row groups
 
 // y[t, :] = bf16( sum_j w[t, j] * out[slot_of[t, j], :] ), j ascending, fp32 sum, one rounding.

@@ -60,7 +60,10 @@ constexpr size_t kScratchBytes = (size_t)kXcds * kMaxWgsPerXcd * kPartialFloats 
 // tile, slot tile within the group.  32 consecutive tiles (what the 32 CUs of one XCD work on at
 // one time) are then about 8 slot tiles x 4 feature tiles of one expert: 12 distinct operand tiles
 // feed 32 workgroups through the XCD's L2.
-constexpr int kGroup = 8;
+#ifndef MOE_GEMM_GROUP
+#define MOE_GEMM_GROUP 8
+#endif
+constexpr int kGroup = MOE_GEMM_GROUP;
 
 __device__ inline int count_tiles(const int32_t* __restrict__ offs, int E, int n_ftiles) {
     int total = 0;
