@@ -15,15 +15,14 @@
 namespace moe {
 namespace {
 
-// Pipeline shape of the two GEMMs: K step and number of LDS stages (STAGES * 512 rows * BK * 2 bytes of LDS).
-#ifndef MOE_GEMM_BK
-#define MOE_GEMM_BK 32
-#endif
-#ifndef MOE_GEMM_STAGES
-#define MOE_GEMM_STAGES 4
-#endif
-constexpr int kBK = MOE_GEMM_BK;
-constexpr int kStages = MOE_GEMM_STAGES;
+// Pipeline shapes of the two GEMMs (K step, LDS stages: STAGES * 512 rows * BK * 2 bytes).
+//   long calls:  K step 64, two stages.  Every global->LDS load instruction then moves whole 128-byte
+//                lines, which the load path handles measurably faster than the half lines of K step 32
+//                (gemm1 -4.5 % at 4096 tokens); the next K step is requested at once after each barrier.
+//   short calls: K step 32, four stages: three K steps of lookahead matter more when the weights
+//                arrive from HBM with nothing to hide them behind (about 100 tokens: +8 % the other way).
+// MOE_GEMM_BK / MOE_GEMM_STAGES force one shape for every call (tuning).
+constexpr int kLongCallTokens = 256;
 constexpr int kWT = 2, kWW = 4;  // wavefront grid: slot groups x weight-row groups
 
 // y[t, :] = bf16( sum_j w[t, j] * out[slot_of[t, j], :] ), j ascending, fp32 sum, one rounding.
@@ -52,17 +51,15 @@ __global__ __launch_bounds__(256) void combine_bf16(const float* __restrict__ ou
     }
 }
 
-}  // namespace
-
-hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w, const void* w1,
-                           const void* w3, const void* w2, void* y, const int32_t* offs,
-                           const int32_t* row_of_slot, const int32_t* slot_of, void* act, float* out,
-                           int32_t* sync, float* partial, hipStream_t stream) {
-    static_assert(gg::kSyncInts == kGemmSyncInts && gg::kScratchBytes == kGemmScratchBytes, "workspace layout");
-    using G1 = gg::Gemm<2, kBK, kStages, kWT, kWW>;
-    using G2 = gg::Gemm<1, kBK, kStages, kWT, kWW>;
-    auto k1 = gg::grouped_gemm_kernel<2, kBK, kStages, kWT, kWW>;
-    auto k2 = gg::grouped_gemm_kernel<1, kBK, kStages, kWT, kWW>;
+// gemm1 (+ SwiGLU) and gemm2 with one pipeline shape.
+template <int BK, int STAGES>
+hipError_t launch_gemms(const moe_shape_t& s, const uint16_t* x, const uint16_t* act_in, const uint16_t* w1,
+                        const uint16_t* w3, const uint16_t* w2, const int32_t* offs, const int32_t* row_of_slot,
+                        void* act, float* out, int32_t* sync, float* partial, hipStream_t stream) {
+    using G1 = gg::Gemm<2, BK, STAGES, kWT, kWW>;
+    using G2 = gg::Gemm<1, BK, STAGES, kWT, kWW>;
+    auto k1 = gg::grouped_gemm_kernel<2, BK, STAGES, kWT, kWW>;
+    auto k2 = gg::grouped_gemm_kernel<1, BK, STAGES, kWT, kWW>;
     static bool configured = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
@@ -75,14 +72,36 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
     }
     // One persistent workgroup per CU (a multiple of the 8 XCDs); the kernels size their own work from `offs`.
     const int grid = max(gg::kXcds, compute_units() / gg::kXcds * gg::kXcds);
-    k1<<<grid, G1::kThreads, G1::kLdsBytes, stream>>>(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w1),
-                                                      static_cast<const uint16_t*>(w3), offs, row_of_slot, s.n_experts,
-                                                      s.top_k, s.ffn, s.hidden, act, sync, partial);
+    k1<<<grid, G1::kThreads, G1::kLdsBytes, stream>>>(x, w1, w3, offs, row_of_slot, s.n_experts, s.top_k, s.ffn,
+                                                      s.hidden, act, sync, partial);
     stage_mark(stream, kStageGemm1);
-    k2<<<grid, G2::kThreads, G2::kLdsBytes, stream>>>(static_cast<const uint16_t*>(act), static_cast<const uint16_t*>(w2),
-                                                      nullptr, offs, row_of_slot, s.n_experts, s.top_k, s.hidden, s.ffn,
-                                                      out, sync + gg::kSyncInts, partial);
+    k2<<<grid, G2::kThreads, G2::kLdsBytes, stream>>>(act_in, w2, nullptr, offs, row_of_slot, s.n_experts, s.top_k,
+                                                      s.hidden, s.ffn, out, sync + gg::kSyncInts, partial);
     stage_mark(stream, kStageGemm2);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w, const void* w1,
+                           const void* w3, const void* w2, void* y, const int32_t* offs,
+                           const int32_t* row_of_slot, const int32_t* slot_of, void* act, float* out,
+                           int32_t* sync, float* partial, hipStream_t stream) {
+    static_assert(gg::kSyncInts == kGemmSyncInts && gg::kScratchBytes == kGemmScratchBytes, "workspace layout");
+    const uint16_t* xs = static_cast<const uint16_t*>(x);
+    const uint16_t* a16 = static_cast<const uint16_t*>(act);
+    const uint16_t *p1 = static_cast<const uint16_t*>(w1), *p3 = static_cast<const uint16_t*>(w3),
+                   *p2 = static_cast<const uint16_t*>(w2);
+    hipError_t e;
+#if defined(MOE_GEMM_BK) && defined(MOE_GEMM_STAGES)
+    e = launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+#else
+    if (tokens >= kLongCallTokens)
+        e = launch_gemms<64, 2>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+    else
+        e = launch_gemms<32, 4>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+#endif
+    if (e != hipSuccess) return e;
     combine_bf16<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, static_cast<uint16_t*>(y));
     stage_mark(stream, kStageCombine);
     return hipGetLastError();

@@ -257,8 +257,11 @@ struct Gemm {
 
         // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
         // computed, and within a k16 step one at a time between MFMAs (see step() below).
-        static_assert(kLoads % kKSteps == 0, "loads per stage must split evenly over the k16 steps");
-        constexpr int kLoadsPerPart = kLoads / kKSteps;
+        // With only two stages the next K step is requested at once, in the first k16 step, so that it
+        // has the whole K step to arrive; with a deeper ring the requests are spread over all k16 steps.
+        constexpr int kDmaParts = STAGES == 2 ? 1 : kKSteps;
+        static_assert(kLoads % kDmaParts == 0, "loads per stage must split evenly over the k16 steps that issue them");
+        constexpr int kLoadsPerPart = kLoads / kDmaParts;
         auto dma_one = [&](int stage, int kt, int l) {
             const uint32_t base = lds0 + (uint32_t)stage * kStageBytes;
             dma16(gp[l] + (size_t)kt * kRowBytes,
@@ -299,7 +302,7 @@ struct Gemm {
         // the matrix pipe also has work while the wavefronts re-synchronise.
         static_assert(kKSteps % 2 == 0, "fragment buffers alternate per k16 step");
         constexpr int kM = kWF * kTF, kR = kWF + kTF;
-        static_assert(kR + kLoadsPerPart <= kM, "a step has one slot per MFMA for its reads and loads");
+        static_assert(kLoadsPerPart <= kM, "a step has one slot per MFMA for its loads");
         bf16x8 tf[2][kTF], wf[2][kWF];
         auto read_one = [&](int stage, int ks, int buf, int idx) {
             const unsigned char* st = lds + stage * kStageBytes;
@@ -322,7 +325,8 @@ struct Gemm {
                         acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
                 }
                 if (decltype(read)::value && m < kR) read_one(rstage, rks, rbuf, m);
-                if (m >= kM - kLoadsPerPart && dma) dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
+                if (m >= kM - kLoadsPerPart && dma && dpart < kDmaParts)
+                    dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -356,7 +360,7 @@ struct Gemm {
                 }
             }
         }
-        step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, 0);
+        step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, kDmaParts);
 
         // ---- split tiles: publish this piece; the last piece to arrive sums them all in part order.
         if (parts > 1) {
