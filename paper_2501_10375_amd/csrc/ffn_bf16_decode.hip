@@ -91,6 +91,9 @@ __device__ unsigned long long g_dec_trace[512][8];
 #define DEC_TRACE(slot) do { } while (0)
 #endif
 // Phase-1 tiles are dealt to the workgroups round-robin (1) or in contiguous runs (0).
+#ifndef MOE_DEC_ROT
+#define MOE_DEC_ROT 37
+#endif
 #ifndef MOE_DEC_TILE_RR
 #define MOE_DEC_TILE_RR 1
 #endif
@@ -389,10 +392,18 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
     // This workgroup's tiles, numbered n = 0 .. n_mine - 1 in ascending tile order.
     const int tiles_per_wg = (total_tiles + gridDim.x - 1) / gridDim.x;
     const int t0 = blockIdx.x * tiles_per_wg;
+    // Round n deals tiles [n * grid, (n + 1) * grid) to the workgroups rotated by n * kRot, so that a
+    // workgroup (and with it an XCD, which owns every 8th workgroup) does not always meet the same
+    // residue of the tile number modulo 8, i.e. the same address bits: how fast an XCD streams
+    // depends on which part of memory it reads.
+    constexpr int kRot = MOE_DEC_ROT;
+    const int grid = gridDim.x, bx = blockIdx.x;
+    auto slot_in_round = [&](int n) { return (bx + n * kRot) % grid; };
+    const int full_rounds = total_tiles / grid;
     const int n_mine = MOE_DEC_TILE_RR
-                           ? ((int)blockIdx.x < total_tiles ? (total_tiles - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0)
+                           ? full_rounds + (full_rounds * grid + slot_in_round(full_rounds) < total_tiles ? 1 : 0)
                            : max(0, min(total_tiles, t0 + tiles_per_wg) - t0);
-    auto tile_id = [&](int n) { return MOE_DEC_TILE_RR ? (int)blockIdx.x + n * (int)gridDim.x : t0 + n; };
+    auto tile_id = [&](int n) { return MOE_DEC_TILE_RR ? n * grid + slot_in_round(n) : t0 + n; };
 
     const KSplit ks(H / 64, wave);  // ks.per <= kXSteps
     const int n_valid = ks.n_valid, kstride = ks.stride;
