@@ -144,7 +144,10 @@ struct Swz<32> {  // 64-byte rows, 4 pieces; four rows span the 64 banks
     static __device__ inline int piece(int row, int chunk) { return chunk ^ ((row >> 2) & 3); }
 };
 
-template <int NMAT, int BK, int STAGES, int WT, int WW>
+// SKIP: slot fragments of a ragged tile that hold no valid slot are skipped (their LDS reads and
+// MFMAs).  That pays when many experts are cold (most tiles ragged), but it puts every MFMA behind a
+// scalar branch, which costs a little when nearly all tiles are full; the launcher decides.
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP>
 struct Gemm {
     static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
     static constexpr int kThreads = kWaves * 64;
@@ -309,7 +312,7 @@ struct Gemm {
             if (idx < kWF)
                 wf[buf][idx] = *reinterpret_cast<const bf16x8*>(
                     st + kTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
-            else if (idx - kWF < n_tf)
+            else if (!SKIP || idx - kWF < n_tf)
                 tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
                     st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
         };
@@ -321,7 +324,7 @@ struct Gemm {
             for (int m = 0; m < kM; ++m) {
                 if (decltype(mfma)::value) {
                     const int i = m / kWF, j = m % kWF;
-                    if (i < n_tf)
+                    if (!SKIP || i < n_tf)
                         acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
                 }
                 if (decltype(read)::value && m < kR) read_one(rstage, rks, rbuf, m);
@@ -478,7 +481,7 @@ struct Gemm {
     }
 };
 
-template <int NMAT, int BK, int STAGES, int WT, int WW>
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP>
 __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uint16_t* __restrict__ tok_base,
                                                                     const uint16_t* __restrict__ wa,
                                                                     const uint16_t* __restrict__ wb,
@@ -488,7 +491,7 @@ __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uin
                                                                     int32_t* __restrict__ sync,
                                                                     float* __restrict__ scratch) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
-    Gemm<NMAT, BK, STAGES, WT, WW>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
+    Gemm<NMAT, BK, STAGES, WT, WW, SKIP>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
                                                lds_dyn);
 }
 
