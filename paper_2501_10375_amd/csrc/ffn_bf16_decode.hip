@@ -13,23 +13,26 @@
 //   * every workgroup evaluates the gate for all tokens itself (the gate is
 //     64-128 KB and the arithmetic is the same everywhere, so all workgroups
 //     agree bit for bit); workgroup 0 publishes indices, weights and counts;
-//   * no permutation and no LDS staging of weights: every weight byte is used
-//     by exactly one wavefront, so it is loaded straight into MFMA operand
-//     registers with 16-byte loads;
+//   * no token permutation and no LDS staging of weights: every weight byte is
+//     used by exactly one wavefront, so it is loaded straight into registers
+//     with 16-byte loads, consecutive lanes on consecutive addresses;
 //   * every load instruction covers 8 weight rows x 128 contiguous bytes (whole
 //     cache lines; 64-byte pieces stream measurably slower).  The natural
 //     operand layout of v_mfma_f32_16x16x32_bf16 would give 16 rows x 64 bytes,
 //     so the 16 operand rows are used as 8 weight rows x 2 halves of a 64-wide
-//     K step instead: a second load fetches the next 8 weight rows with the
-//     halves swapped, a per-lane select recombines the two loads into one
+//     K step instead: a second load fetches the next 8 weight rows, a cross-lane
+//     rearrangement and a per-lane select recombine the two loads into one
 //     operand holding the lower K half of all 16 weight rows and one holding
 //     the upper half (with rows i and i ^ 8 exchanged), and two MFMAs with the
 //     matching halves of the tokens accumulate them; the two accumulators are
 //     added, after undoing the row exchange with a cross-lane move, when the
 //     tile is finished;
 //   * the tokens of an expert form the 16 columns of the MFMA, so up to 16
-//     tokens share one pass over the weights; lanes whose column has no token
-//     issue no load;
+//     tokens share one pass over the weights;
+//   * every load of the streaming loops is unconditional (steps, tiles and token
+//     columns that do not exist re-read a valid address and are multiplied by
+//     zeros or ignored), so the compiler can count outstanding loads and wait
+//     for exactly the step it needs;
 //   * each wavefront keeps P steps of loads in flight in a rotating register
 //     window (software pipeline unrolled P times) that runs across tile
 //     boundaries, and the barrier at a tile's end waits for LDS only, so the
@@ -181,10 +184,18 @@ __device__ void build_groups(Groups<NC>& g, const int* idx, int A, int E) {
     __syncthreads();
 }
 
-__device__ inline u32x4 load16(const uint16_t* p, bool on) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (on) v = *reinterpret_cast<const u32x4*>(p);
-    return v;
+// Every load of the streaming loops is unconditional: a load under a branch cannot be counted by
+// the compiler, which then waits for ALL outstanding loads before each use (s_waitcnt vmcnt(0)) and
+// the software pipeline degenerates into "request P steps, wait for all of them".  Steps, tiles and
+// token columns that do not exist therefore re-read a valid address of the same operand (a cache
+// hit), and their contribution is removed by zeroing the token operand when it is used.
+__device__ inline u32x4 load16(const uint16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+__device__ inline u32x4 keep_if(bool on, u32x4 v) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = on ? v[i] : 0u;
+    return r;
 }
 
 __device__ inline bf16x8 pick(bool first, u32x4 a, u32x4 b) {
@@ -211,21 +222,48 @@ __device__ inline f32x4 fold_halves(f32x4 acc1, f32x4 acc2) {
 }
 
 // Per-lane element offsets inside a tile of 16 weight rows and a 64-element K step.
+//
+// Loads are issued with consecutive lanes on consecutive addresses: lane s reads the 16-byte piece
+// s % 8 of row s / 8 (8 rows x 128 contiguous bytes per instruction).  The MFMA wants row
+// lane % 16 and K group lane / 16 in each lane, which scatters the lanes of every quad over four
+// rows; loading in that order costs the address path four cache-line lookups where one would do
+// (measured: an isolated tile takes 3.4 times as long, the saturated stream 3-4 % longer).  So the
+// loaded registers are rearranged across lanes afterwards (ds_bpermute, no LDS memory involved):
+// MFMA lane l = (i = l % 16, kq = l / 16) takes, from the load of rows 0-7, row i % 8 and piece
+// (i >= 8 ? 4 : 0) + kq, and from the load of rows 8-15, row 8 + i % 8 and piece (i >= 8 ? 0 : 4) + kq
+// (the two K halves swapped), which is the pair of layouts mfma_operands() recombines.
 struct LaneMap {
-    int row_lo, row_hi;  // weight rows (within the tile) of the two loads
-    int k_lo, k_hi;      // element offset of this lane's 8 elements inside the K step
-    int kq8;             // element offset of the lane's token operand inside each 32-element half
+    int row_lo, row_hi;    // weight rows (within the tile) this lane loads in the two loads
+    int k_ld;              // element offset of the 8 elements it loads inside the K step
+    int perm_lo, perm_hi;  // byte index (4 * source lane) for ds_bpermute after the two loads
+    int kq8;               // element offset of the lane's token operand inside each 32-element half
     bool upper;
     __device__ explicit LaneMap(int lane) {
         const int i = lane & 15, kq = lane >> 4;
         upper = i >= 8;
-        row_lo = i & 7;
-        row_hi = 8 + (i & 7);
-        k_lo = ((upper ? 4 : 0) + kq) * 8;
-        k_hi = ((upper ? 0 : 4) + kq) * 8;
+        row_lo = lane >> 3;
+        row_hi = 8 + (lane >> 3);
+        k_ld = (lane & 7) * 8;
+        perm_lo = ((i & 7) * 8 + (upper ? 4 : 0) + kq) * 4;
+        perm_hi = ((i & 7) * 8 + (upper ? 0 : 4) + kq) * 4;
         kq8 = kq * 8;
     }
 };
+
+__device__ inline u32x4 gather_lanes(int byte_index, u32x4 v) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(byte_index, (int)v[i]);
+    return r;
+}
+
+// From the raw loads of rows 0-7 and rows 8-15 of a K step: `first` holds the lower K half of all
+// 16 weight rows (MFMA row i = weight row i), `second` the upper half with rows i and i ^ 8 exchanged.
+__device__ inline void mfma_operands(const LaneMap& lm, u32x4 lo_raw, u32x4 hi_raw, bf16x8& first, bf16x8& second) {
+    const u32x4 lo = gather_lanes(lm.perm_lo, lo_raw), hi = gather_lanes(lm.perm_hi, hi_raw);
+    first = pick(lm.upper, hi, lo);
+    second = pick(lm.upper, lo, hi);
+}
 
 template <int NC>
 struct Smem {
@@ -261,36 +299,33 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
     const int n_valid = ks.n_valid, kstride = ks.stride;
     const int spt = (ks.per + P - 1) / P * P;  // steps per tile, padded to the pipeline depth
     const long total_q = (long)(t1 - t0) * spt;
+    const size_t k0 = n_valid > 0 ? ks.k0 : 0;  // a wavefront without steps re-reads the row's start
 
     u32x4 lo1[P], hi1[P], lo3[P], hi3[P], xa[P][NC], xb[P][NC];
     // Issue-side state: the next step to request and the row bases of its tile.
     int is = 0, itile = t0;
     size_t wlo = 0, whi = 0, xbase[NC];
-    bool xcol[NC];
     auto enter_tile = [&]() {
         const int d = itile / tiles_per_expert;
         const int f0 = (itile - d * tiles_per_expert) * 16;
         const size_t row0 = (size_t)g.expert[d] * F + f0;
-        const size_t k0 = ks.k0;
-        wlo = (row0 + lm.row_lo) * H + k0 + lm.k_lo;
-        whi = (row0 + lm.row_hi) * H + k0 + lm.k_hi;
+        wlo = (row0 + lm.row_lo) * H + k0 + lm.k_ld;
+        whi = (row0 + lm.row_hi) * H + k0 + lm.k_ld;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            xcol[c] = col + 16 * c < g.cnt[d];
-            xbase[c] = (size_t)(xcol[c] ? g.assign[d][col + 16 * c] / k : 0) * H + k0 + lm.kq8;
-        }
+        for (int c = 0; c < NC; ++c)  // columns without a token read the expert's first token (result unused)
+            xbase[c] = (size_t)(g.assign[d][col + 16 * c < g.cnt[d] ? col + 16 * c : 0] / k) * H + k0 + lm.kq8;
     };
     enter_tile();
-    auto issue = [&](int i) {
-        const bool on = is < n_valid;
-        lo1[i] = load16(p.w1 + wlo + is * kstride, on);
-        hi1[i] = load16(p.w1 + whi + is * kstride, on);
-        lo3[i] = load16(p.w3 + wlo + is * kstride, on);
-        hi3[i] = load16(p.w3 + whi + is * kstride, on);
+    auto issue = [&](int i) {  // requests past the last tile re-read it
+        const size_t off = (size_t)(is < n_valid ? is : 0) * kstride;
+        lo1[i] = load16(p.w1 + wlo + off);
+        hi1[i] = load16(p.w1 + whi + off);
+        lo3[i] = load16(p.w3 + wlo + off);
+        hi3[i] = load16(p.w3 + whi + off);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            xa[i][c] = load16(p.x + xbase[c] + is * kstride, on && xcol[c]);
-            xb[i][c] = load16(p.x + xbase[c] + is * kstride + 32, on && xcol[c]);
+            xa[i][c] = load16(p.x + xbase[c] + off);
+            xb[i][c] = load16(p.x + xbase[c] + off + 32);
         }
         if (++is == spt) {
             is = 0;
@@ -308,18 +343,20 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            const bf16x8 a1 = pick(lm.upper, hi1[i], lo1[i]), a2 = pick(lm.upper, lo1[i], hi1[i]);
-            const bf16x8 a3 = pick(lm.upper, hi3[i], lo3[i]), a4 = pick(lm.upper, lo3[i], hi3[i]);
+            bf16x8 a1, a2, a3, a4;
+            mfma_operands(lm, lo1[i], hi1[i], a1, a2);
+            mfma_operands(lm, lo3[i], hi3[i], a3, a4);
+            const bool real = cs + i < n_valid;  // a padding step multiplies zeros
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const bf16x8 b1 = __builtin_bit_cast(bf16x8, xa[i][c]);
-                const bf16x8 b2 = __builtin_bit_cast(bf16x8, xb[i][c]);
+                const bf16x8 b1 = __builtin_bit_cast(bf16x8, keep_if(real, xa[i][c]));
+                const bf16x8 b2 = __builtin_bit_cast(bf16x8, keep_if(real, xb[i][c]));
                 g1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, g1[c], 0, 0, 0);
                 g2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b2, g2[c], 0, 0, 0);
                 u1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b1, u1[c], 0, 0, 0);
                 u2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a4, b2, u2[c], 0, 0, 0);
             }
-            if (q + P + i < total_q) issue(i);
+            issue(i);
         }
         cs += P;
         if (cs == spt) {
@@ -407,108 +444,110 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
 
     const KSplit ks(H / 64, wave);  // ks.per <= kXSteps
     const int n_valid = ks.n_valid, kstride = ks.stride;
-    const size_t k0 = ks.k0;
+    const size_t k0 = n_valid > 0 ? ks.k0 : 0;  // a wavefront without steps re-reads the row's start
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    int par = 0;
+    if (n_mine == 0) return;
 
-    for (int seg0 = 0; seg0 < n_mine;) {  // a segment = this workgroup's tiles of one expert
-        const int d = tile_id(seg0) / tiles_per_expert;
-        int seg1 = seg0 + 1;
-        while (seg1 < n_mine && tile_id(seg1) / tiles_per_expert == d) ++seg1;
-        const int cnt = g.cnt[d];
-        const size_t erow0 = (size_t)g.expert[d] * F;
-
-        // token fragments of this expert
-        u32x4 xr[kXSteps][NC][2];
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const bool on = col + 16 * c < cnt;
-            const uint16_t* xp = p.x + (size_t)(on ? g.assign[d][col + 16 * c] / k : 0) * H + k0 + lm.kq8;
-#pragma unroll
-            for (int s = 0; s < kXSteps; ++s) {
-                xr[s][c][0] = load16(xp + s * kstride, on && s < n_valid);
-                xr[s][c][1] = load16(xp + s * kstride + 32, on && s < n_valid);
-            }
+    // Weight stream over this workgroup's tiles, P steps ahead, across expert boundaries; requests
+    // past the last tile re-read it.
+    u32x4 lo1[P], hi1[P], lo3[P], hi3[P];
+    int is = 0, itile = 0;
+    size_t wlo = 0, whi = 0;
+    auto enter_tile = [&]() {
+        const int id = tile_id(min(itile, n_mine - 1));
+        const int d = id / tiles_per_expert;
+        const size_t row0 = (size_t)g.expert[d] * F + (id - d * tiles_per_expert) * 16;
+        wlo = (row0 + lm.row_lo) * H + k0 + lm.k_ld;
+        whi = (row0 + lm.row_hi) * H + k0 + lm.k_ld;
+    };
+    enter_tile();
+    auto issue = [&](int i) {
+        const size_t off = (size_t)(is < n_valid ? is : 0) * kstride;
+        lo1[i] = load16(p.w1 + wlo + off);
+        hi1[i] = load16(p.w1 + whi + off);
+        lo3[i] = load16(p.w3 + wlo + off);
+        hi3[i] = load16(p.w3 + whi + off);
+        if (++is == kXSteps) {
+            is = 0;
+            ++itile;
+            enter_tile();
         }
+    };
+#pragma unroll
+    for (int i = 0; i < P; ++i) issue(i);
 
-        // weight stream over the tiles [seg0, seg1), P steps ahead
-        u32x4 lo1[P], hi1[P], lo3[P], hi3[P];
-        int is = 0, itile = seg0;
-        size_t wlo = 0, whi = 0;
-        auto enter_tile = [&]() {
-            const int f0 = (tile_id(itile) - d * tiles_per_expert) * 16;
-            wlo = (erow0 + f0 + lm.row_lo) * H + k0 + lm.k_lo;
-            whi = (erow0 + f0 + lm.row_hi) * H + k0 + lm.k_hi;
-        };
-        enter_tile();
-        auto issue = [&](int i) {
-            const bool on = is < n_valid && itile < seg1;
-            lo1[i] = load16(p.w1 + wlo + is * kstride, on);
-            hi1[i] = load16(p.w1 + whi + is * kstride, on);
-            lo3[i] = load16(p.w3 + wlo + is * kstride, on);
-            hi3[i] = load16(p.w3 + whi + is * kstride, on);
-            if (++is == kXSteps) {
-                is = 0;
-                if (++itile < seg1) enter_tile();
-            }
-        };
-#pragma unroll
-        for (int i = 0; i < P; ++i) issue(i);
-
-        for (int ctile = seg0; ctile < seg1; ++ctile) {
-            f32x4 g1[NC], g2[NC], u1[NC], u2[NC];
-#pragma unroll
-            for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
-#pragma unroll
-            for (int s = 0; s < kXSteps; ++s) {
-                const int i = s % P;
-                const bf16x8 a1 = pick(lm.upper, hi1[i], lo1[i]), a2 = pick(lm.upper, lo1[i], hi1[i]);
-                const bf16x8 a3 = pick(lm.upper, hi3[i], lo3[i]), a4 = pick(lm.upper, lo3[i], hi3[i]);
-#pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    const bf16x8 b1 = __builtin_bit_cast(bf16x8, xr[s][c][0]);
-                    const bf16x8 b2 = __builtin_bit_cast(bf16x8, xr[s][c][1]);
-                    g1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, g1[c], 0, 0, 0);
-                    g2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b2, g2[c], 0, 0, 0);
-                    u1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b1, u1[c], 0, 0, 0);
-                    u2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a4, b2, u2[c], 0, 0, 0);
-                }
-                issue(i);  // requests past the segment's last tile are switched off inside
-            }
-            // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
-            // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
+    u32x4 xr[kXSteps][NC][2];  // token fragments of the current expert
+    int cur_d = -1, par = 0;
+    for (int ctile = 0; ctile < n_mine; ++ctile) {
+        const int id = tile_id(ctile);
+        const int d = id / tiles_per_expert;
+        const int f0 = (id - d * tiles_per_expert) * 16;
+        const int cnt = g.cnt[d];
+        if (d != cur_d) {
+            cur_d = d;
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                sm.red[par][wave][0][c][lane] = fold_halves(g1[c], g2[c]);
-                sm.red[par][wave][1][c][lane] = fold_halves(u1[c], u2[c]);
-            }
-            lds_barrier();
-            const int f0 = (tile_id(ctile) - d * tiles_per_expert) * 16;
-            for (int item = tid; item < 128 * NC; item += kThreads) {
-                const int c = item >> 7, pl = item & 63, rp = (item >> 6) & 1;
-                const int tok = (pl & 15) + 16 * c;
-                if (tok < cnt) {
-                    float o[2];
+                // columns without a token read the expert's first token (their results are unused)
+                const uint16_t* xp = p.x + (size_t)(g.assign[d][col + 16 * c < cnt ? col + 16 * c : 0] / k) * H + k0 + lm.kq8;
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        float gs = 0.f, us = 0.f;
-#pragma unroll
-                        for (int w = 0; w < kWaves; ++w) {
-                            gs += sm.red[par][w][0][c][pl][2 * rp + h];
-                            us += sm.red[par][w][1][c][pl][2 * rp + h];
-                        }
-                        o[h] = swiglu(gs, us);
-                    }
-                    // device-scope (write-through) store: read by other workgroups after the grid barrier
-                    uint32_t* dst = reinterpret_cast<uint32_t*>(p.act + (size_t)g.assign[d][tok] * F + f0 +
-                                                                4 * (pl >> 4) + 2 * rp);
-                    __hip_atomic_store(dst, pack_bf16x2(o[0], o[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int s = 0; s < kXSteps; ++s) {
+                    const size_t off = (size_t)(s < n_valid ? s : 0) * kstride;
+                    xr[s][c][0] = keep_if(s < n_valid, load16(xp + off));
+                    xr[s][c][1] = keep_if(s < n_valid, load16(xp + off + 32));
                 }
             }
-            if (Smem<NC>::kRedBufs == 1) lds_barrier();
-            par = (par + 1) % Smem<NC>::kRedBufs;
         }
-        seg0 = seg1;
+        f32x4 g1[NC], g2[NC], u1[NC], u2[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
+#pragma unroll
+        for (int s = 0; s < kXSteps; ++s) {
+            const int i = s % P;
+            bf16x8 a1, a2, a3, a4;
+            mfma_operands(lm, lo1[i], hi1[i], a1, a2);
+            mfma_operands(lm, lo3[i], hi3[i], a3, a4);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const bf16x8 b1 = __builtin_bit_cast(bf16x8, xr[s][c][0]);
+                const bf16x8 b2 = __builtin_bit_cast(bf16x8, xr[s][c][1]);
+                g1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, b1, g1[c], 0, 0, 0);
+                g2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, b2, g2[c], 0, 0, 0);
+                u1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a3, b1, u1[c], 0, 0, 0);
+                u2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a4, b2, u2[c], 0, 0, 0);
+            }
+            issue(i);
+        }
+        // Tile done: fold the 8 K-slices.  MFMA 16x16 result: lane holds column (token)
+        // lane & 15 and rows (features) 4 * (lane / 16) + r, r = 0..3.
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            sm.red[par][wave][0][c][lane] = fold_halves(g1[c], g2[c]);
+            sm.red[par][wave][1][c][lane] = fold_halves(u1[c], u2[c]);
+        }
+        lds_barrier();
+        for (int item = tid; item < 128 * NC; item += kThreads) {
+            const int c = item >> 7, pl = item & 63, rp = (item >> 6) & 1;
+            const int tok = (pl & 15) + 16 * c;
+            if (tok < cnt) {
+                float o[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    float gs = 0.f, us = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        gs += sm.red[par][w][0][c][pl][2 * rp + h];
+                        us += sm.red[par][w][1][c][pl][2 * rp + h];
+                    }
+                    o[h] = swiglu(gs, us);
+                }
+                // device-scope (write-through) store: read by other workgroups after the grid barrier
+                uint32_t* dst = reinterpret_cast<uint32_t*>(p.act + (size_t)g.assign[d][tok] * F + f0 +
+                                                            4 * (pl >> 4) + 2 * rp);
+                __hip_atomic_store(dst, pack_bf16x2(o[0], o[1]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (Smem<NC>::kRedBufs == 1) lds_barrier();
+        par = (par + 1) % Smem<NC>::kRedBufs;
     }
 }
 
@@ -531,7 +570,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     const int spt = (ks.per + P - 1) / P * P;
     const int D = g.n_active;
     const long total_q = (long)my_tiles * D * spt;
-    const size_t k0 = ks.k0;
+    const size_t k0 = n_valid > 0 ? ks.k0 : 0;  // a wavefront without steps re-reads the row's start
 
     // ---- everything this workgroup stored to `act` has left the CU; announce it
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -546,14 +585,14 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     size_t wlo = 0, whi = 0;
     auto enter_w = [&]() {
         const size_t row0 = (size_t)g.expert[wd] * H + wt * 16;
-        wlo = (row0 + lm.row_lo) * F + k0 + lm.k_lo;
-        whi = (row0 + lm.row_hi) * F + k0 + lm.k_hi;
+        wlo = (row0 + lm.row_lo) * F + k0 + lm.k_ld;
+        whi = (row0 + lm.row_hi) * F + k0 + lm.k_ld;
     };
     enter_w();
-    auto issue_w = [&](int i) {
-        const bool on = ws < n_valid;
-        lo[i] = load16(p.w2 + wlo + ws * kstride, on);
-        hi[i] = load16(p.w2 + whi + ws * kstride, on);
+    auto issue_w = [&](int i) {  // requests past the last tile re-read it
+        const size_t off = (size_t)(ws < n_valid ? ws : 0) * kstride;
+        lo[i] = load16(p.w2 + wlo + off);
+        hi[i] = load16(p.w2 + whi + off);
         if (++ws == spt) {
             ws = 0;
             if (++wd == D) {
@@ -566,21 +605,18 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     // act-side issue state (the operand does not depend on the h tile)
     int as = 0, ad = 0;
     size_t abase[NC];
-    bool acol[NC];
     auto enter_a = [&]() {
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            acol[c] = col + 16 * c < g.cnt[ad];
-            abase[c] = (size_t)(acol[c] ? g.assign[ad][col + 16 * c] : 0) * F + k0 + lm.kq8;
-        }
+        for (int c = 0; c < NC; ++c)  // columns without a token read the expert's first token (result unused)
+            abase[c] = (size_t)g.assign[ad][col + 16 * c < g.cnt[ad] ? col + 16 * c : 0] * F + k0 + lm.kq8;
     };
     enter_a();
     auto issue_a = [&](int i) {
-        const bool on = as < n_valid;
+        const size_t off = (size_t)(as < n_valid ? as : 0) * kstride;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            aa[i][c] = load16(p.act + abase[c] + as * kstride, on && acol[c]);
-            ab[i][c] = load16(p.act + abase[c] + as * kstride + 32, on && acol[c]);
+            aa[i][c] = load16(p.act + abase[c] + off);
+            ab[i][c] = load16(p.act + abase[c] + off + 32);
         }
         if (++as == spt) {
             as = 0;
@@ -615,16 +651,18 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     for (long q = 0; q < total_q; q += P) {
 #pragma unroll
         for (int i = 0; i < P; ++i) {
-            const bf16x8 a1 = pick(lm.upper, hi[i], lo[i]), a2 = pick(lm.upper, lo[i], hi[i]);
+            bf16x8 a1, a2;
+            mfma_operands(lm, lo[i], hi[i], a1, a2);
+            const bool real = cs + i < n_valid;  // a padding step multiplies zeros
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                acc1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, aa[i][c]), acc1[c], 0, 0, 0);
-                acc2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8, ab[i][c]), acc2[c], 0, 0, 0);
+                acc1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, __builtin_bit_cast(bf16x8, keep_if(real, aa[i][c])),
+                                                                  acc1[c], 0, 0, 0);
+                acc2[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2, __builtin_bit_cast(bf16x8, keep_if(real, ab[i][c])),
+                                                                  acc2[c], 0, 0, 0);
             }
-            if (q + P + i < total_q) {
-                issue_w(i);
-                issue_a(i);
-            }
+            issue_w(i);
+            issue_a(i);
         }
         cs += P;
         if (cs == spt) {
