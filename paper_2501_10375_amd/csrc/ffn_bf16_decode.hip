@@ -212,6 +212,42 @@ __device__ inline void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// ---- grid-wide rendezvous between the two GEMMs, in two stages.
+// The active experts are split into a first group (the lower half of the ascending list, group A)
+// and the rest (group B).  Phase 1 visits a workgroup's tiles in expert order, phase 2 its experts
+// in the same order, so a workgroup raises flag A when it has stored its last intermediate values
+// of group A, goes on with group B, raises flag B, and in phase 2 needs everybody's flag A only
+// before its first group-A operand and everybody's flag B only before its first group-B operand.
+// By then the others have normally been past that point for tens of microseconds, so nobody
+// waits for the slowest workgroup between the phases (a single rendezvous costs the mean
+// workgroup about 6 us of a 128 us call: the spread of the phase-1 finishing times).
+// A flag is "raised" when it holds the launch's epoch; the two flag arrays are kFlagStride apart.
+constexpr int kFlagStride = kDecodeFlagInts / 2;
+
+// All of this workgroup's stores to `act` so far have left the CU; then raise `flag`.
+__device__ inline void announce(uint32_t* flag, uint32_t epoch) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits (all threads) until the n flags all hold `epoch`.  The spin is bounded, so the kernel ends
+// even if the workgroups never become co-resident.  Global loads already in flight stay in flight.
+__device__ inline void await_flags(const uint32_t* flags, int n, uint32_t epoch) {
+    if (threadIdx.x < 64) {
+        for (int it = 0; it < (1 << 22); ++it) {
+            bool all = true;
+            for (int i = threadIdx.x; i < n; i += 64)
+                all &= __hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == epoch;
+            if (__all(all)) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    asm volatile("" ::: "memory");
+    lds_barrier();
+    asm volatile("" ::: "memory");  // no load of `act` may be moved above the rendezvous
+}
+
 // acc1 holds MFMA row i = weight row i, acc2 holds MFMA row i = weight row i ^ 8; MFMA rows
 // 4 * (lane / 16) + r sit in lane, so row i ^ 8 is the same register of lane ^ 32.
 __device__ inline f32x4 fold_halves(f32x4 acc1, f32x4 acc2) {
@@ -280,7 +316,7 @@ struct Smem {
 // ---- phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f]) over this workgroup's share
 // of the (active expert, 16-feature tile) list.
 template <int P, int NC>
-__device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
+__device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, bool& a_open) {
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
@@ -339,8 +375,13 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
     f32x4 g1[NC], g2[NC], u1[NC], u2[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) g1[c] = g2[c] = u1[c] = u2[c] = zero;
+    const int d_a = (g.n_active + 1) / 2;  // experts [0, d_a) of the active list are group A
     int cs = 0, ctile = t0;
     for (long q = 0; q < total_q; q += P) {
+        if (a_open && cs == 0 && ctile / tiles_per_expert >= d_a) {  // group A is complete here
+            announce(&p.flags[blockIdx.x], p.epoch);
+            a_open = false;
+        }
 #pragma unroll
         for (int i = 0; i < P; ++i) {
             bf16x8 a1, a2, a3, a4;
@@ -416,7 +457,7 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm) {
 // counters cost more than they saved.)
 constexpr int kXSteps = 8;
 template <int P, int NC>
-__device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
+__device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, bool& a_open) {
     static_assert(kXSteps % P == 0, "the weight ring must divide a tile");
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -477,12 +518,17 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
     for (int i = 0; i < P; ++i) issue(i);
 
     u32x4 xr[kXSteps][NC][2];  // token fragments of the current expert
+    const int d_a = (g.n_active + 1) / 2;  // experts [0, d_a) of the active list are group A
     int cur_d = -1, par = 0;
     for (int ctile = 0; ctile < n_mine; ++ctile) {
         const int id = tile_id(ctile);
         const int d = id / tiles_per_expert;
         const int f0 = (id - d * tiles_per_expert) * 16;
         const int cnt = g.cnt[d];
+        if (a_open && d >= d_a) {  // this workgroup's part of group A is complete
+            announce(&p.flags[blockIdx.x], p.epoch);
+            a_open = false;
+        }
         if (d != cur_d) {
             cur_d = d;
 #pragma unroll
@@ -555,7 +601,7 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm) {
 // w[a] * (act[a] . w2[e, h]) for this workgroup's 16-row tiles of h.  The first P steps of weight
 // loads are issued before the grid-wide barrier that `act` has to wait for.
 template <int P, int NC>
-__device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
+__device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, bool a_open) {
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
@@ -572,10 +618,15 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     const long total_q = (long)my_tiles * D * spt;
     const size_t k0 = n_valid > 0 ? ks.k0 : 0;  // a wavefront without steps re-reads the row's start
 
-    // ---- everything this workgroup stored to `act` has left the CU; announce it
+    // ---- everything this workgroup stored to `act` has left the CU: raise flag B (and flag A, if
+    // phase 1 did not get to it)
+    const int d_a = (D + 1) / 2;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (tid == 0) __hip_atomic_store(&p.flags[blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        if (a_open) __hip_atomic_store(&p.flags[blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&p.flags[kFlagStride + blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     DEC_TRACE(3);
     if (total_q == 0) return;
 
@@ -604,6 +655,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
     };
     // act-side issue state (the operand does not depend on the h tile)
     int as = 0, ad = 0;
+    bool b_open = d_a < D;  // group B still has to be awaited
     size_t abase[NC];
     auto enter_a = [&]() {
 #pragma unroll
@@ -621,24 +673,19 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm) {
         if (++as == spt) {
             as = 0;
             if (++ad == D) ad = 0;
+            if (b_open && ad >= d_a) {  // the next operand belongs to group B
+                await_flags(p.flags + kFlagStride, n_wgs, p.epoch);
+                b_open = false;
+                DEC_TRACE(6);
+            }
             enter_a();
         }
     };
 #pragma unroll
     for (int i = 0; i < P; ++i) issue_w(i);
 
-    // ---- grid-wide barrier: wait until every workgroup's flag carries this launch's epoch.
-    // The spin is bounded, so the kernel ends even if workgroups never become co-resident.
-    if (tid < 64) {
-        for (int it = 0; it < (1 << 22); ++it) {
-            bool all = true;
-            for (int i = tid; i < n_wgs; i += 64)
-                all &= __hip_atomic_load(&p.flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.epoch;
-            if (__all(all)) break;
-            __builtin_amdgcn_s_sleep(1);
-        }
-    }
-    __syncthreads();
+    // ---- group A of the intermediate is needed now
+    await_flags(p.flags, n_wgs, p.epoch);
     DEC_TRACE(4);
 #pragma unroll
     for (int i = 0; i < P; ++i) issue_a(i);
@@ -745,9 +792,10 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     DEC_TRACE(1);
     build_groups<NC>(sm.g, sm.idx, A, p.E);
     DEC_TRACE(2);
-    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm);
-    else gemm1_phase<P1, NC>(p, sm);
-    gemm2_phase<P2, NC>(p, sm);
+    bool a_open = true;  // flag A not raised yet
+    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm, a_open);
+    else gemm1_phase<P1, NC>(p, sm, a_open);
+    gemm2_phase<P2, NC>(p, sm, a_open);
     DEC_TRACE(5);
 }
 
@@ -786,7 +834,7 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     p.H = s.hidden;
     p.F = s.ffn;
     const int max_tiles1 = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
-    const int grid = min(min(compute_units(), kDecodeFlagInts), max(max_tiles1, s.hidden / 16));
+    const int grid = min(min(compute_units(), kFlagStride), max(max_tiles1, s.hidden / 16));
     if (route != nullptr) {
         decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, true, 1><<<grid, kThreads, 0, stream>>>(p);
     } else if (tokens <= 16) {
