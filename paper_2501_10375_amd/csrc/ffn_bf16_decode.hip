@@ -34,25 +34,31 @@
 //     zeros or ignored), so the compiler can count outstanding loads and wait
 //     for exactly the step it needs;
 //   * each wavefront keeps P steps of loads in flight in a rotating register
-//     window (software pipeline unrolled P times) that runs across tile
-//     boundaries, and the barrier at a tile's end waits for LDS only, so the
-//     stream never drains;
+//     window (software pipeline unrolled P times) that runs across tile and
+//     expert boundaries, and the barrier at a tile's end waits for LDS only, so
+//     the stream never drains.  With 2048 wavefronts on the chip a shallow
+//     window is enough and measurably better than a deep one (P = 1 for the
+//     first GEMM, 2 for the second; 4 and 8 lose 2-3 %);
 //   * the 8 wavefronts of a workgroup split K (interleaved 64-element steps),
 //     and their partial 16 x 16 tiles are summed through LDS in a fixed order
 //     (deterministic);
 //   * between the two GEMMs every workgroup needs the whole intermediate
-//     vector: a grid-wide barrier made of one arrival flag per workgroup, each
-//     set to a per-launch epoch, so the flags never need clearing and no
-//     read-modify-write atomic is contended.  The intermediate is written with
+//     vector of an expert before it multiplies by that expert's W2: a
+//     grid-wide rendezvous made of one arrival flag per workgroup, each set to
+//     a per-launch epoch, so the flags never need clearing and no
+//     read-modify-write atomic is contended.  The experts are taken in two
+//     groups with a rendezvous each (see announce()), which the workgroups
+//     reach long after the others have passed, so nobody waits for the slowest
+//     workgroup in the middle of the call.  The intermediate is written with
 //     device-scope (write-through) stores, so it has reached memory when the
 //     flag is raised, and it is read with ordinary loads only after the
-//     barrier: no L2 holds an older copy, because caches are invalidated when
-//     a kernel starts and nothing reads the intermediate before the barrier.
-//     This keeps the barrier free of cache write-backs and invalidations (a
-//     device-scope fence issued by every wavefront of the grid costs tens of
-//     microseconds here).  The first P steps of the second GEMM's weights are
-//     requested before the barrier is awaited, so the stream continues across
-//     it.
+//     rendezvous: no L2 holds an older copy, because caches are invalidated
+//     when a kernel starts and nothing reads a group's intermediate before its
+//     rendezvous.  This keeps the rendezvous free of cache write-backs and
+//     invalidations (a device-scope fence issued by every wavefront of the grid
+//     costs tens of microseconds here).  The first P steps of the second GEMM's
+//     weights are requested before the first rendezvous is awaited, so the
+//     stream continues across it.
 //
 //   phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f])   a = t*k + j, e = idx[a]
 //   phase 2: y[t, h]   = sum over the token's experts (ascending expert id) of
@@ -72,10 +78,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // Pipeline depths (64-element K steps of loads in flight per wavefront) of the two GEMM phases.
 #ifndef MOE_DEC_P1
-#define MOE_DEC_P1 2
+#define MOE_DEC_P1 1
 #endif
 #ifndef MOE_DEC_P2
-#define MOE_DEC_P2 4
+#define MOE_DEC_P2 2
 #endif
 
 constexpr int kWaves = 8;
@@ -840,7 +846,7 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     } else if (tokens <= 16) {
         decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 1><<<grid, kThreads, 0, stream>>>(p);
     } else {
-        decode_layer_kernel<2, 4, false, 2><<<grid, kThreads, 0, stream>>>(p);
+        decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 2><<<grid, kThreads, 0, stream>>>(p);
     }
     stage_mark(stream, kStageFused);
     return hipGetLastError();
