@@ -122,6 +122,13 @@ __device__ inline void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
+// 16-byte store that is written through to memory (device scope), as an agent-scope atomic store is.
+// The compiler does not track hazards of instructions inside inline asm: a store of more than 8
+// bytes needs a wait state before its data registers may be overwritten, hence the s_nop.
+__device__ inline void store16_through(float* p, f32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
+
 // Workgroup barrier that orders LDS traffic only (no wait on outstanding global loads).
 __device__ inline void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -368,6 +375,9 @@ struct Gemm {
         // ---- split tiles: publish this piece; the last piece to arrive sums them all in part order.
         if (parts > 1) {
             float* mine = partials + (size_t)part * kPartialFloats;
+            // The stores below are issued from inline asm, which the compiler's hazard bookkeeping does
+            // not cover: leave the last MFMAs time to write their results (19 wait states at most).
+            asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
             for (int j = 0; j < kWF; ++j)
 #pragma unroll
@@ -377,21 +387,24 @@ struct Gemm {
                         f32x4 v;
 #pragma unroll
                         for (int c = 0; c < 4; ++c) v[c] = acc[j][i][q * 4 + c];
-                        *reinterpret_cast<f32x4*>(mine + ((size_t)((j * kTF + i) * 4 + q) * kThreads + tid) * 4) = v;
+                        store16_through(mine + ((size_t)((j * kTF + i) * 4 + q) * kThreads + tid) * 4, v);
                     }
-            // The barrier waits until every wavefront's stores have reached this XCD's L2.  One
-            // wavefront then counts the arrival with a device-scope acquire-release atomic: its
-            // release writes the whole L2's dirty lines back before the count becomes visible and
-            // its acquire drops stale lines before the pieces are read.  (Cache maintenance is per
-            // cache, not per wavefront, and costs tens of microseconds when all wavefronts of the
-            // grid issue it, so exactly one wavefront per workgroup does.)
+            // The pieces are written through to memory (device-scope stores), so once every wavefront's
+            // stores have been acknowledged (vmcnt 0, then the barrier) one relaxed atomic can count the
+            // arrival: no cache has to be written back.  Only the workgroup that sums the pieces
+            // invalidates its caches before it reads them.  (An acquire-release atomic per arrival
+            // would add an L2 write-back each time, tens of microseconds in all.)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             int* flag = reinterpret_cast<int*>(lds);
-            if (tid == 0) *flag = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) *flag = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
             const bool is_last = *flag == parts - 1;
             __syncthreads();  // everyone has read the flag before LDS is reused
             if (!is_last) return;  // only ever in the last round, so nothing follows for this workgroup
+            // one wavefront drops whatever this CU's cache may hold of the pieces (an invalidate, no write-back)
+            if (tid == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            __syncthreads();
 #pragma unroll
             for (int j = 0; j < kWF; ++j)
 #pragma unroll
