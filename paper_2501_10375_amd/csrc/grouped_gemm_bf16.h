@@ -112,8 +112,10 @@ __device__ inline void xcd_rendezvous(int32_t* counter, int target) {
 }
 
 // 16 bytes per lane from `gptr` to LDS byte address lds_base + lane * 16 (lds_base wave-uniform).
+// (The compiler does not insert hazard wait states inside inline asm: an LDS-DMA load that reads M0
+// needs one after the scalar write of M0, hence the s_nop.)
 __device__ inline void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
 
 template <int N>
