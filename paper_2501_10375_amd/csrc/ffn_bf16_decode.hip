@@ -143,6 +143,10 @@ struct DecodeArgs {
     int accumulate;
     const int32_t* idx_in;
     const float* w_in;
+    // prediction with the next layer's gate (wg_next may be null): pred_out [T, k]
+    const uint16_t* wg_next;
+    const float* bias_next;
+    int32_t* pred_out;
     const uint16_t *w1, *w3, *w2;
     uint16_t* act;          // [T*k, F] workspace
     uint16_t* y;            // [T, H]
@@ -802,6 +806,15 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm, a_open);
     else gemm1_phase<P1, NC>(p, sm, a_open);
     gemm2_phase<P2, NC>(p, sm, a_open);
+    if (ROUTE && p.wg_next != nullptr && blockIdx.x == gridDim.x - 1) {
+        // The prediction for the next layer, which nothing in this call waits for: one workgroup
+        // evaluates the next gate once its share of the experts is done (same routine as the routing
+        // above, so the result is the one a separate routing call gives).
+        __syncthreads();  // the reduction buffer is free
+        route_tokens_wg<uint16_t>(p.x, p.wg_next, p.bias_next, p.T, p.H, p.E, p.k, sm.route,
+                                  reinterpret_cast<float*>(&sm.red[0][0][0][0][0]));
+        if (tid < A) p.pred_out[tid] = sm.route.idx[tid];
+    }
     DEC_TRACE(5);
 }
 
@@ -821,6 +834,9 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
         p.w_out = route->wts;
         p.counts = route->counts;
         p.accumulate = route->accumulate;
+        p.wg_next = static_cast<const uint16_t*>(route->w_gate_next);
+        p.bias_next = route->bias_next;
+        p.pred_out = route->pred_idx;
     } else {
         p.idx_in = topk_idx;
         p.w_in = topk_w;

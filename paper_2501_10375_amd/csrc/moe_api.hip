@@ -310,16 +310,10 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
         return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, nullptr, stream));
     stage_call_begin(stream);
     if (decode_path(*shape, tokens)) {
-        // One kernel routes and runs the experts; the prediction gate, which nothing downstream in
-        // this call waits for, follows in a small launch of its own.
-        const DecodeRoute r = {w_gate, gate_bias, topk_idx, topk_w, counts, accumulate};
-        hipError_t e = launch_decode_layer(*shape, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags,
-                                           stream);
-        if (e != hipSuccess || w_gate_next == nullptr) return dev(e);
-        GateArgs gn[1] = {{w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
-        e = launch_route_small(*shape, tokens, x, gn, 1, nullptr, 0, nullptr, stream);
-        stage_mark(stream, kStageRoute);
-        return dev(e);
+        // One kernel routes, runs the experts and (in one of its workgroups, at the end) evaluates the
+        // prediction gate.
+        const DecodeRoute r = {w_gate, gate_bias, topk_idx, topk_w, counts, accumulate, w_gate_next, gate_bias_next, pred_idx};
+        return dev(launch_decode_layer(*shape, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags, stream));
     }
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;

@@ -124,6 +124,11 @@ struct DecodeRoute {
     float* wts;
     int32_t* counts;
     int accumulate;
+    // optional prediction (the next layer's gate on the same hidden states): evaluated by one
+    // workgroup after its share of the experts; pred_idx [tokens, top_k]
+    const void* w_gate_next;
+    const float* bias_next;
+    int32_t* pred_idx;
 };
 hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
                                const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
