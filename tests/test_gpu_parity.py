@@ -102,6 +102,29 @@ def test_repeatable_and_independent_of_workspace_contents(T):
         assert torch.equal(res["idx"], i0) and torch.equal(res["counts"], c0)
 
 
+@pytest.mark.parametrize("T,H,F,E,k", [(1, 256, 512, 8, 2), (6, 256, 512, 8, 2), (16, 128, 320, 8, 8), (3, 64, 64, 4, 1),
+                                       (24, 256, 512, 8, 2), (300, 256, 512, 8, 2), (600, 1024, 2048, 8, 2)])
+def test_sequence_of_calls_on_one_workspace_small_shapes(T, H, F, E, k):
+    """Calls with changing inputs share one workspace at sizes where everything stays in the caches
+    between launches: what an earlier call left there (intermediate values, K-split pieces,
+    rendezvous flags and counters) must never be what a later call reads.  Every call is compared
+    bit for bit with the same call on a fresh workspace filled with a byte pattern."""
+    dtype = torch.bfloat16
+    d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, seed=3, zipf_s=1.2, with_next=True)
+    shape = moe.make_shape(H, F, E, k, dtype)
+    shared = moe.LayerOutputs(shape, T, dtype, DEV, predict=True)
+    for step in range(8):
+        call = dict(d, x=synth.normal((T, H), 3000 + step, synth.TID_X, 1.0, dtype, DEV))
+        got = moe.run_layer(shape, call, shared, predict=True)
+        y, idx, pred = got["y"].clone(), got["idx"].clone(), got["pred_idx"].clone()
+        fresh = moe.LayerOutputs(shape, T, dtype, DEV, predict=True)
+        fresh.workspace.fill_(0x5A)
+        ref = moe.run_layer(shape, call, fresh, predict=True)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, ref["idx"]) and torch.equal(pred, ref["pred_idx"]), f"step {step}"
+        assert torch.equal(y.view(torch.int16), ref["y"].view(torch.int16)), f"step {step}"
+
+
 def test_counts_accumulate_over_calls_and_zero_tokens(oracle):
     H, F, E, k, dtype = 256, 512, 8, 2, torch.bfloat16
     d, shape, out, res = _run(40, H, F, E, k, dtype)
