@@ -466,6 +466,16 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, bool& a_op
 // the load pipeline full, which is as coarse as the imbalance it is meant to remove, and the
 // counters cost more than they saved.)
 constexpr int kXSteps = 8;
+// Workgroups that take part in phase 1: as many as are needed for the busiest one's tile count,
+// ceil(tiles / ceil(tiles / grid)); 800 tiles go to 200 workgroups with 4 each rather than to 256
+// with 3 or 4.  The HBM stream is the shared resource, so a balanced share over fewer workgroups
+// ends when the bytes are through, while an unbalanced one ends with a few workgroups streaming
+// alone at their latency-bound rate (800-tile case: phase 1 ends at 44 instead of 47 us; a deeper
+// load window for the fewer streams did not help further).
+__device__ inline int phase1_participants(int total_tiles, int grid) {
+    const int busiest = (total_tiles + grid - 1) / grid;
+    return (total_tiles + busiest - 1) / max(busiest, 1);
+}
 template <int P, int NC>
 __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, bool& a_open) {
     static_assert(kXSteps % P == 0, "the weight ring must divide a tile");
@@ -480,16 +490,19 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, bool&
     // This workgroup's tiles, numbered n = 0 .. n_mine - 1 in ascending tile order.
     const int tiles_per_wg = (total_tiles + gridDim.x - 1) / gridDim.x;
     const int t0 = blockIdx.x * tiles_per_wg;
-    // Round n deals tiles [n * grid, (n + 1) * grid) to the workgroups rotated by n * kRot, so that a
+    // Only as many workgroups take part as are needed for the busiest one's tile count (see
+    // phase1_participants()).
+    // Round n deals tiles [n * g1, (n + 1) * g1) to the participants rotated by n * kRot, so that a
     // workgroup (and with it an XCD, which owns every 8th workgroup) does not always meet the same
     // residue of the tile number modulo 8, i.e. the same address bits: how fast an XCD streams
     // depends on which part of memory it reads.
     constexpr int kRot = MOE_DEC_ROT;
-    const int grid = gridDim.x, bx = blockIdx.x;
+    const int bx = blockIdx.x;
+    const int grid = MOE_DEC_TILE_RR ? phase1_participants(total_tiles, gridDim.x) : (int)gridDim.x;  // g1
     auto slot_in_round = [&](int n) { return (bx + n * kRot) % grid; };
-    const int full_rounds = total_tiles / grid;
+    const int full_rounds = grid > 0 ? total_tiles / grid : 0;
     const int n_mine = MOE_DEC_TILE_RR
-                           ? full_rounds + (full_rounds * grid + slot_in_round(full_rounds) < total_tiles ? 1 : 0)
+                           ? (bx < grid ? full_rounds + (full_rounds * grid + slot_in_round(full_rounds) < total_tiles ? 1 : 0) : 0)
                            : max(0, min(total_tiles, t0 + tiles_per_wg) - t0);
     auto tile_id = [&](int n) { return MOE_DEC_TILE_RR ? n * grid + slot_in_round(n) : t0 + n; };
 
