@@ -274,7 +274,13 @@ struct Gemm {
         constexpr int kDmaParts = STAGES == 2 ? 1 : kKSteps;
         static_assert(kLoads % kDmaParts == 0, "loads per stage must split evenly over the k16 steps that issue them");
         constexpr int kLoadsPerPart = kLoads / kDmaParts;
+        // SKIP: a wavefront whose 32 slot rows all lie past the tile's last slot stages no slot rows (the
+        // fragments they would feed are skipped as well): a ragged tile then moves its weights plus only
+        // its own slot rows through the load path, which is what bounds tiles of cold experts.
+        static_assert(!SKIP || kStageRows == 32, "a wavefront stages exactly one 32-slot fragment");
+        const bool stage_tok = !SKIP || wave * kStageRows < rows;
         auto dma_one = [&](int stage, int kt, int l) {
+            if (SKIP && l < kLoadsPerOperand && !stage_tok) return;
             const uint32_t base = lds0 + (uint32_t)stage * kStageBytes;
             dma16(gp[l] + (size_t)kt * kRowBytes,
                   base + (l < kLoadsPerOperand ? stage_off_tok : stage_off_w) + (l % kLoadsPerOperand) * 1024);
@@ -358,8 +364,9 @@ struct Gemm {
                 const int kt = kt0 + s;
                 if (kt < KT) {
                     // K step kt must have landed; up to STAGES - 2 younger ones may stay in flight
-                    if (kt + STAGES - 2 < KT) wait_vmcnt<(STAGES - 2) * kLoads>();
-                    else wait_vmcnt<0>();
+                    if (kt + STAGES - 2 >= KT) wait_vmcnt<0>();
+                    else if (stage_tok) wait_vmcnt<(STAGES - 2) * kLoads>();
+                    else wait_vmcnt<(STAGES - 2) * kLoadsPerOperand>();  // this wavefront issues weight loads only
                     lds_barrier();
                     const bool more = kt + STAGES - 1 < KT;
                     const int ns = (s + STAGES - 1) % STAGES;
