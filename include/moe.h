@@ -36,9 +36,10 @@
  *   - Expert selection: softmax over all experts in fp32, the top_k largest
  *     probabilities in descending order (equal probabilities: lower expert
  *     index first), their weights renormalised to sum to one.
- *   - bf16 calls with at most 16 tokens run as one persistent kernel (one
- *     workgroup per compute unit) whose workgroups wait for one another
- *     between the two expert GEMMs.  The wait is bounded, so a call always
+ *   - bf16 calls with at most 32 tokens run their experts (at most 16 tokens:
+ *     the whole layer) as one persistent kernel, one workgroup per compute
+ *     unit, whose workgroups wait for one another between the two expert
+ *     GEMMs.  The wait is bounded, so a call always
  *     ends, but its result is only defined when the device can hold the whole
  *     grid at once, i.e. when no other kernel occupies compute units for the
  *     duration of the call.  (The prefill-size grouped GEMM is persistent too;
