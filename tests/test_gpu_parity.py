@@ -56,6 +56,28 @@ def test_bf16_decode_path(oracle, T, H, F, E, k):
     print(r)
 
 
+def _random_shapes(n, seed):
+    """Seeded sweep over legal shapes: token counts on both sides of every path boundary (16, 32,
+    256), widths that do not divide the tile sizes, few and many experts, every top_k."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for i in range(n):
+        T = int(rng.choice([1, 2, 3, 7, 15, 16, 17, 24, 31, 32, 33, 48, 63, 64, 80, 127, 200, 255, 256, 257, 300]))
+        H = 64 * int(rng.integers(1, 9))
+        F = 64 * int(rng.integers(1, 25))
+        E = int(rng.choice([1, 2, 3, 4, 5, 8, 11, 16, 24, 32, 64]))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        shapes.append((T, H, F, E, k, i))
+    return shapes
+
+
+@pytest.mark.parametrize("T,H,F,E,k,seed", _random_shapes(36, 20250110))
+def test_bf16_random_shapes(oracle, T, H, F, E, k, seed):
+    d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16, seed=seed, zipf=1.2 if seed % 3 else None)
+    r = check_layer(oracle, d, shape, res, torch.bfloat16, label=f"bf16 random T={T} H={H} F={F} E={E} k={k}")
+    print(r)
+
+
 @pytest.mark.parametrize("T,H,F,E,k", [(100, 128, 192, 8, 2), (5, 64, 128, 4, 2), (130, 256, 64, 16, 3)])
 def test_fp32_path(oracle, T, H, F, E, k):
     d, shape, out, res = _run(T, H, F, E, k, torch.float32)
