@@ -250,10 +250,11 @@ def main():
             xs = synth.normal((Td, H), 1000, synth.TID_X, 1.0, dtype, dev)
             outs = moe.LayerOutputs(shape, Td, dtype, dev, predict=False)
             calls = [dict(L, x=xs, wg_next=None, bias_next=None) for L in layers]
+            prepared = [moe.PreparedLayerCall(shape, c, outs, predict=False) for c in calls]  # arguments marshalled once
             state = {"i": 0}
 
             def dstep():
-                moe.run_layer(shape, calls[state["i"] % len(calls)], outs, predict=False)
+                prepared[state["i"] % len(prepared)]()
                 state["i"] += 1
 
             n = max(args.steps, 4 * len(calls))

@@ -174,6 +174,37 @@ def moe_layer(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next
                            _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()), "moe_layer")
 
 
+class PreparedLayerCall:
+    """A moe_layer call whose arguments were checked and marshalled once, for loops that repeat it on
+    the same buffers (a decode step of about 100 microseconds leaves no room for per-call argument
+    checks in Python).  Calling the object enqueues the call on the current stream."""
+
+    def __init__(self, shape: MoeShape, d: dict, out: "LayerOutputs", accumulate: bool = False, predict: bool = True):
+        x = d["x"]
+        T, E, k, H, F = x.shape[0], shape.n_experts, shape.top_k, shape.hidden, shape.ffn
+        dt = x.dtype
+        pred = out.pred_idx[:T] if (predict and d.get("wg_next") is not None) else None
+        y, idx, w = out.y[:T], out.topk_idx[:T], out.topk_w[:T]
+        self._keep = (shape, d, out, y, idx, w, pred)   # the tensors behind the raw pointers
+        self._fn = lib().moe_layer
+        self._args = (ctypes.byref(shape), T, _p(x, None, (T, H), "x"), _p(d["wg"], dt, (E, H), "w_gate"),
+                      _p(d.get("bias"), torch.float32, (E,), "gate_bias"),
+                      _p(d.get("wg_next") if pred is not None else None, dt, (E, H), "w_gate_next"),
+                      _p(d.get("bias_next") if pred is not None else None, torch.float32, (E,), "gate_bias_next"),
+                      _p(d["w1"], dt, (E, F, H), "w1"), _p(d["w3"], dt, (E, F, H), "w3"), _p(d["w2"], dt, (E, H, F), "w2"),
+                      _p(y, dt, (T, H), "y"), _p(idx, torch.int32, (T, k), "topk_idx"),
+                      _p(w, torch.float32, (T, k), "topk_w"), _p(out.counts, torch.int32, (E,), "counts"),
+                      int(bool(accumulate)), _p(pred, torch.int32, (T, k), "pred_idx"),
+                      _p(out.workspace, torch.uint8, None, "workspace"), out.workspace.numel())
+        self.result = {"y": y, "idx": idx, "w": w, "counts": out.counts, "pred_idx": pred}
+
+    def __call__(self):
+        status = self._fn(*self._args, _stream())
+        if status != 0:
+            raise MoeError(status, "moe_layer")
+        return self.result
+
+
 def moe_stage_timing_begin(max_calls: int):
     _check(lib().moe_stage_timing_begin(max_calls), "moe_stage_timing_begin")
 

@@ -147,6 +147,20 @@ def test_sequence_of_calls_on_one_workspace_small_shapes(T, H, F, E, k):
         assert torch.equal(y.view(torch.int16), ref["y"].view(torch.int16)), f"step {step}"
 
 
+def test_prepared_call_equals_run_layer():
+    """The binding's pre-marshalled call object enqueues the same call as run_layer."""
+    T, H, F, E, k, dtype = 6, 256, 512, 8, 2, torch.bfloat16
+    d, shape, out, res = _run(T, H, F, E, k, dtype)
+    y, idx, pred, counts = res["y"].clone(), res["idx"].clone(), res["pred_idx"].clone(), res["counts"].clone()
+    out2 = moe.LayerOutputs(shape, T, dtype, DEV, predict=True)
+    call = moe.PreparedLayerCall(shape, d, out2, predict=True)
+    for _ in range(3):
+        got = call()
+    torch.cuda.synchronize()
+    assert torch.equal(got["idx"], idx) and torch.equal(got["pred_idx"], pred) and torch.equal(got["counts"], counts)
+    assert torch.equal(got["y"].view(torch.int16), y.view(torch.int16))
+
+
 def test_counts_accumulate_over_calls_and_zero_tokens(oracle):
     H, F, E, k, dtype = 256, 512, 8, 2, torch.bfloat16
     d, shape, out, res = _run(40, H, F, E, k, dtype)
