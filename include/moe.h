@@ -16,10 +16,13 @@
  *   - All tensor pointers are DEVICE pointers on the current HIP device, dense
  *     row-major with the last index contiguous, 16-byte aligned.  The caller
  *     owns every buffer, including the workspace; the library allocates
- *     nothing and keeps no state apart from a process-wide launch counter.
+ *     nothing and keeps no state between calls.
  *     The workspace is scratch: its contents never need initialising and are
  *     undefined afterwards.  Two calls that use the same workspace must not
  *     run at the same time (order them on one stream or with events).
+ *   - Every call only enqueues kernels whose arguments depend on nothing but
+ *     the call's own arguments, so a call may be recorded into a HIP graph
+ *     (stream capture) and replayed; moe_stage_timing_* must be off then.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
  *     stream).  Calls validate their arguments on the host, enqueue kernels on
  *     that stream and return without synchronising.  Outputs are valid once

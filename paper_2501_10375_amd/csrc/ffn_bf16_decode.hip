@@ -63,8 +63,6 @@
 //   phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f])   a = t*k + j, e = idx[a]
 //   phase 2: y[t, h]   = sum over the token's experts (ascending expert id) of
 //                        w[a] * (act[a] . w2[e, h]),  fp32, one rounding to bf16
-#include <atomic>
-
 #include "bf16_utils.h"
 #include "moe_internal.h"
 #include "route_device.h"
@@ -150,8 +148,7 @@ struct DecodeArgs {
     const uint16_t *w1, *w3, *w2;
     uint16_t* act;          // [T*k, F] workspace
     uint16_t* y;            // [T, H]
-    uint32_t* flags;        // [gridDim.x] workspace: arrival flags of the grid-wide barrier
-    uint32_t epoch;         // value that marks an arrival in this launch
+    uint32_t* flags;        // workspace: 2 x kFlagStride arrival flags of the two rendezvous, then the epoch word
     int T, k, E, H, F;
 };
 
@@ -232,7 +229,15 @@ __device__ inline void lds_barrier() {
 // waits for the slowest workgroup between the phases (a single rendezvous costs the mean
 // workgroup about 6 us of a 128 us call: the spread of the phase-1 finishing times).
 // A flag is "raised" when it holds the launch's epoch; the two flag arrays are kFlagStride apart.
-constexpr int kFlagStride = kDecodeFlagInts / 2;
+constexpr int kFlagStride = 256;
+// The epoch is a launch count kept in the workspace too (one word after the flags): a launch reads
+// it when it starts and uses count + 1; workgroup 0 stores the new count when it ends, by which time
+// every workgroup has read the old one (workgroup 0 has passed a rendezvous that all of them had to
+// reach).  Flags left by earlier launches carry earlier epochs, and arbitrary memory contents equal
+// the new epoch only by accident, so nothing ever needs clearing; and because no launch argument
+// changes from call to call, a call recorded into a HIP graph can be replayed.
+constexpr int kEpochIndex = 2 * kFlagStride;
+static_assert(kEpochIndex < kDecodeFlagInts, "flags and epoch fit the workspace block");
 
 // All of this workgroup's stores to `act` so far have left the CU; then raise `flag`.
 __device__ inline void announce(uint32_t* flag, uint32_t epoch) {
@@ -326,7 +331,7 @@ struct Smem {
 // ---- phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f]) over this workgroup's share
 // of the (active expert, 16-feature tile) list.
 template <int P, int NC>
-__device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, bool& a_open) {
+__device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t epoch, bool& a_open) {
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
@@ -389,7 +394,7 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, bool& a_op
     int cs = 0, ctile = t0;
     for (long q = 0; q < total_q; q += P) {
         if (a_open && cs == 0 && ctile / tiles_per_expert >= d_a) {  // group A is complete here
-            announce(&p.flags[blockIdx.x], p.epoch);
+            announce(&p.flags[blockIdx.x], epoch);
             a_open = false;
         }
 #pragma unroll
@@ -477,7 +482,7 @@ __device__ inline int phase1_participants(int total_tiles, int grid) {
     return (total_tiles + busiest - 1) / max(busiest, 1);
 }
 template <int P, int NC>
-__device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, bool& a_open) {
+__device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, uint32_t epoch, bool& a_open) {
     static_assert(kXSteps % P == 0, "the weight ring must divide a tile");
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -549,7 +554,7 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, bool&
         const int f0 = (id - d * tiles_per_expert) * 16;
         const int cnt = g.cnt[d];
         if (a_open && d >= d_a) {  // this workgroup's part of group A is complete
-            announce(&p.flags[blockIdx.x], p.epoch);
+            announce(&p.flags[blockIdx.x], epoch);
             a_open = false;
         }
         if (d != cur_d) {
@@ -624,7 +629,7 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, bool&
 // w[a] * (act[a] . w2[e, h]) for this workgroup's 16-row tiles of h.  The first P steps of weight
 // loads are issued before the grid-wide barrier that `act` has to wait for.
 template <int P, int NC>
-__device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, bool a_open) {
+__device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t epoch, bool a_open) {
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15;
@@ -647,8 +652,8 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, bool a_ope
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-        if (a_open) __hip_atomic_store(&p.flags[blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&p.flags[kFlagStride + blockIdx.x], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a_open) __hip_atomic_store(&p.flags[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&p.flags[kFlagStride + blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     DEC_TRACE(3);
     if (total_q == 0) return;
@@ -697,7 +702,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, bool a_ope
             as = 0;
             if (++ad == D) ad = 0;
             if (b_open && ad >= d_a) {  // the next operand belongs to group B
-                await_flags(p.flags + kFlagStride, n_wgs, p.epoch);
+                await_flags(p.flags + kFlagStride, n_wgs, epoch);
                 b_open = false;
                 DEC_TRACE(6);
             }
@@ -708,7 +713,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, bool a_ope
     for (int i = 0; i < P; ++i) issue_w(i);
 
     // ---- group A of the intermediate is needed now
-    await_flags(p.flags, n_wgs, p.epoch);
+    await_flags(p.flags, n_wgs, epoch);
     DEC_TRACE(4);
 #pragma unroll
     for (int i = 0; i < P; ++i) issue_a(i);
@@ -779,6 +784,12 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     __shared__ Smem<NC> sm;
     const int tid = threadIdx.x;
     const int A = p.T * p.k;
+    // The launch's epoch: read before anything of this launch can have changed the word.  What the
+    // flags carry is the epoch mixed with a constant, so that leftovers of other uses of the memory
+    // (small integers, zeros, all-ones) do not look like raised flags.
+    // (Requested here, used after the routing, so its latency costs nothing.)
+    const uint32_t last_count = __hip_atomic_load(&p.flags[kEpochIndex], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::: "memory");
     DEC_TRACE(0);
     for (int i = tid; i < 16 * NC * 16; i += kThreads) sm.yacc[i >> 4][i & 15] = 0.f;
     if (ROUTE) {
@@ -815,10 +826,14 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     DEC_TRACE(1);
     build_groups<NC>(sm.g, sm.idx, A, p.E);
     DEC_TRACE(2);
+    const uint32_t count = (uint32_t)__builtin_amdgcn_readfirstlane((int)last_count) + 1u;
+    const uint32_t epoch = count ^ 0x9E3779B9u;
     bool a_open = true;  // flag A not raised yet
-    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm, a_open);
-    else gemm1_phase<P1, NC>(p, sm, a_open);
-    gemm2_phase<P2, NC>(p, sm, a_open);
+    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm, epoch, a_open);
+    else gemm1_phase<P1, NC>(p, sm, epoch, a_open);
+    gemm2_phase<P2, NC>(p, sm, epoch, a_open);
+    if (blockIdx.x == 0 && tid == 0)  // the next launch counts on from here
+        __hip_atomic_store(&p.flags[kEpochIndex], count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (ROUTE && p.wg_next != nullptr && blockIdx.x == gridDim.x - 1) {
         // The prediction for the next layer, which nothing in this call waits for: one workgroup
         // evaluates the next gate once its share of the experts is done (same routine as the routing
@@ -830,8 +845,6 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     }
     DEC_TRACE(5);
 }
-
-std::atomic<uint32_t> g_epoch{0};
 
 }  // namespace
 
@@ -860,9 +873,6 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     p.act = static_cast<uint16_t*>(act);
     p.y = static_cast<uint16_t*>(y);
     p.flags = flags;
-    uint32_t epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
-    if (epoch == 0) epoch = g_epoch.fetch_add(1, std::memory_order_relaxed) + 1;
-    p.epoch = epoch;
     p.T = tokens;
     p.k = s.top_k;
     p.E = s.n_experts;

@@ -33,7 +33,7 @@ struct WorkspaceLayout {
     size_t row_of_slot;  // int32 [A]            slot -> assignment index t*k + j
     size_t slot_of;      // int32 [A]            assignment index -> slot
     size_t sync;         // int32 [kSyncInts]    rendezvous / arrival counters of the two grouped GEMMs
-    size_t dec_flags;    // uint32 [kDecodeFlagInts]  arrival flags of the decode kernel's two grid-wide rendezvous
+    size_t dec_flags;    // uint32 [kDecodeFlagInts]  arrival flags and launch count of the decode kernel's two grid-wide rendezvous
     size_t route_end;    // bytes needed by routing-only calls
     size_t act;          // dtype [A, F]         silu(W1 x) * (W3 x)
     size_t out;          // fp32  [A, H]         per-assignment expert output
@@ -114,9 +114,9 @@ int compute_units();
 // Decode-size bf16 calls (tokens <= kDecodeMaxTokens): one persistent kernel streams the selected
 // experts' weights.  With `route` it first evaluates the gate (and writes indices, weights and
 // counts); without, it takes topk_idx / topk_w.  `flags` are kDecodeFlagInts words of workspace
-// whose contents need not be initialised (two arrays of kDecodeFlagInts / 2 arrival flags, one per
-// workgroup and rendezvous; the grid is at most kDecodeFlagInts / 2 workgroups).
-constexpr int kDecodeFlagInts = 512;
+// whose contents need not be initialised (two arrays of 256 arrival flags, one per workgroup and
+// rendezvous, and the launch count the flags' epoch is derived from; the grid is at most 256 workgroups).
+constexpr int kDecodeFlagInts = 2 * 256 + 16;
 struct DecodeRoute {
     const void* w_gate;
     const float* bias;
