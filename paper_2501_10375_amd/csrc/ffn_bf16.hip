@@ -15,15 +15,18 @@
 namespace moe {
 namespace {
 
-// Pipeline shapes of the two GEMMs (K step, LDS stages: STAGES * 512 rows * BK * 2 bytes).
-//   long calls:  K step 64, two stages.  Every global->LDS load instruction then moves whole 128-byte
-//                lines, which the load path handles measurably faster than the half lines of K step 32
-//                (gemm1 -4.5 % at 4096 tokens); the next K step is requested at once after each barrier.
-//   short calls: K step 32, four stages: three K steps of lookahead matter more when the weights
-//                arrive from HBM with nothing to hide them behind (about 100 tokens: +8 % the other way).
-// MOE_GEMM_BK / MOE_GEMM_STAGES force one shape for every call (tuning).
-constexpr int kLongCallTokens = 256;
-constexpr int kRaggedRowsPerExpert = 512;  // mean routed rows per expert below which tiles count as mostly ragged
+// Tile and pipeline shapes of the two GEMMs (slot rows per tile, K step, LDS stages).  Both move whole
+// 128-byte lines per global->LDS load instruction (K step 64); they differ in how much of a K step's
+// operand traffic can be in flight:
+//   full calls (most slot tiles full):  256 slots x 256 weight rows, two 64 KB stages.  The larger tile
+//       moves the fewest operand bytes per flop, which is what counts when the MFMAs are the work
+//       (4096 tokens: 7 % faster than the other shape), but only the next K step can be in flight.
+//   ragged calls (few routed rows per expert): 128 slots x 256 weight rows, three 48 KB stages, and
+//       empty slot fragments skipped.  Two K steps in flight hide the load latency that bounds a tile
+//       with little arithmetic, and half-height tiles pad cold experts less (40 to 1024 tokens:
+//       1-17 % faster, Phi-shaped layer up to 16 %).
+// MOE_GEMM_BK / MOE_GEMM_STAGES (/ MOE_GEMM_BT) force one shape for every call (tuning).
+constexpr int kRaggedRowsPerExpert = 512;  // mean routed rows per expert below which a call counts as ragged
 constexpr int kWT = 2, kWW = 4;  // wavefront grid: slot groups x weight-row groups
 
 // y[t, :] = bf16( sum_j w[t, j] * out[slot_of[t, j], :] ), j ascending, fp32 sum, one rounding.
@@ -53,14 +56,14 @@ __global__ __launch_bounds__(256) void combine_bf16(const float* __restrict__ ou
 }
 
 // gemm1 (+ SwiGLU) and gemm2 with one pipeline shape.
-template <int BK, int STAGES, bool SKIP>
+template <int BK, int STAGES, bool SKIP, int BT = gg::kBT>
 hipError_t launch_gemms(const moe_shape_t& s, const uint16_t* x, const uint16_t* act_in, const uint16_t* w1,
                         const uint16_t* w3, const uint16_t* w2, const int32_t* offs, const int32_t* row_of_slot,
                         void* act, float* out, int32_t* sync, float* partial, hipStream_t stream) {
-    using G1 = gg::Gemm<2, BK, STAGES, kWT, kWW, SKIP>;
-    using G2 = gg::Gemm<1, BK, STAGES, kWT, kWW, SKIP>;
-    auto k1 = gg::grouped_gemm_kernel<2, BK, STAGES, kWT, kWW, SKIP>;
-    auto k2 = gg::grouped_gemm_kernel<1, BK, STAGES, kWT, kWW, SKIP>;
+    using G1 = gg::Gemm<2, BK, STAGES, kWT, kWW, SKIP, BT>;
+    using G2 = gg::Gemm<1, BK, STAGES, kWT, kWW, SKIP, BT>;
+    auto k1 = gg::grouped_gemm_kernel<2, BK, STAGES, kWT, kWW, SKIP, BT>;
+    auto k2 = gg::grouped_gemm_kernel<1, BK, STAGES, kWT, kWW, SKIP, BT>;
     static bool configured = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
@@ -94,19 +97,16 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
     const uint16_t *p1 = static_cast<const uint16_t*>(w1), *p3 = static_cast<const uint16_t*>(w3),
                    *p2 = static_cast<const uint16_t*>(w2);
     hipError_t e;
-    // Few routed rows per expert: most slot tiles are ragged, skipping their empty fragments pays
-    // (Phi-shaped layer at 2048 tokens: gemm1 -5 %); many: nearly all tiles are full and the
-    // branch-free loop is faster (Mixtral-shaped layer at 4096 tokens: gemm2 -2.7 %).
     const bool ragged = (long)tokens * s.top_k < (long)s.n_experts * kRaggedRowsPerExpert;
 #if defined(MOE_GEMM_BK) && defined(MOE_GEMM_STAGES)
-    e = ragged ? launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, true>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream)
-               : launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, false>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+#ifndef MOE_GEMM_BT
+#define MOE_GEMM_BT 256
+#endif
+    e = ragged ? launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, true, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream)
+               : launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, false, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
 #else
-    if (tokens >= kLongCallTokens)
-        e = ragged ? launch_gemms<64, 2, true>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream)
-                   : launch_gemms<64, 2, false>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
-    else
-        e = launch_gemms<32, 4, true>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+    e = ragged ? launch_gemms<64, 3, true, 128>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream)
+               : launch_gemms<64, 2, false, 256>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
 #endif
     if (e != hipSuccess) return e;
     combine_bf16<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, static_cast<uint16_t*>(y));

@@ -1,14 +1,14 @@
 // Grouped bf16 GEMM for the expert FFN on the CDNA4 matrix cores (device code).
 //
-// Computes, per (expert, 256-slot tile, feature tile),
+// Computes, per (expert, slot tile of BT = 256 or 128 slots, feature tile),
 //   NMAT = 2 (gemm1): act[slot, f] = silu(tok[slot] . wa[e, f]) * (tok[slot] . wb[e, f])   (bf16 out)
 //   NMAT = 1 (gemm2): out[slot, n] = tok[slot] . wa[e, n]                                  (fp32 out)
 // where tok rows are gathered rows of x (gemm1) or rows of act (gemm2), and every
 // operand is K-contiguous ("row . row" contraction, no transposes anywhere).
 //
 // Organisation (gfx950):
-//   * Tile 256 slots x 256 weight rows (NMAT = 2: 128 features of each matrix), K in steps of BK.
-//     WT x WW wavefronts (slot groups x weight-row groups); each owns (256/WT) x (256/WW) outputs
+//   * Tile BT slots x 256 weight rows (NMAT = 2: 128 features of each matrix), K in steps of BK.
+//     WT x WW wavefronts (slot groups x weight-row groups); each owns (BT/WT) x (256/WW) outputs
 //     as v_mfma_f32_32x32x16_bf16 tiles.  Weights are the MFMA "A" operand, slot rows the "B"
 //     operand, so a lane ends up holding 4 consecutive output features of one slot.
 //   * Operand tiles go HBM/L2 -> LDS directly (global_load_lds_dwordx4, no register staging), in a
@@ -40,7 +40,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int kBT = 256;   // slots per tile
+constexpr int kBT = 256;   // most slots per tile (the template parameter BT is 256 or 128)
 constexpr int kBW = 256;   // weight rows per tile (all matrices together)
 constexpr int kXcds = 8;
 constexpr int kMaxWgsPerXcd = 32;  // persistent grid: at most 8 x 32 workgroups
@@ -65,19 +65,19 @@ constexpr size_t kScratchBytes = (size_t)kXcds * kMaxWgsPerXcd * kPartialFloats 
 #endif
 constexpr int kGroup = MOE_GEMM_GROUP;
 
-__device__ inline int count_tiles(const int32_t* __restrict__ offs, int E, int n_ftiles) {
+__device__ inline int count_tiles(const int32_t* __restrict__ offs, int E, int n_ftiles, int bt) {
     int total = 0;
-    for (int i = 0; i < E; ++i) total += (offs[i + 1] - offs[i] + kBT - 1) / kBT;
+    for (int i = 0; i < E; ++i) total += (offs[i + 1] - offs[i] + bt - 1) / bt;
     return total * n_ftiles;
 }
 
-__device__ inline void tile_of(const int32_t* __restrict__ offs, int E, int n_ftiles, int id, int& e, int& slot0,
+__device__ inline void tile_of(const int32_t* __restrict__ offs, int E, int n_ftiles, int bt, int id, int& e, int& slot0,
                                int& rows, int& ft) {
     int acc = 0;
     e = 0; slot0 = 0; rows = 1; ft = 0;
     for (int i = 0; i < E; ++i) {
         const int c = offs[i + 1] - offs[i];
-        const int mt = (c + kBT - 1) / kBT;
+        const int mt = (c + bt - 1) / bt;
         const int tiles = mt * n_ftiles;
         if (id < acc + tiles) {
             const int local = id - acc;
@@ -87,8 +87,8 @@ __device__ inline void tile_of(const int32_t* __restrict__ offs, int E, int n_ft
             ft = in_grp / gsize;
             const int m = grp * kGroup + (in_grp - ft * gsize);
             e = i;
-            slot0 = offs[i] + m * kBT;
-            rows = min(kBT, c - m * kBT);
+            slot0 = offs[i] + m * bt;
+            rows = min(bt, c - m * bt);
             return;
         }
         acc += tiles;
@@ -156,21 +156,26 @@ struct Swz<32> {  // 64-byte rows, 4 pieces; four rows span the 64 banks
 // SKIP: slot fragments of a ragged tile that hold no valid slot are skipped (their LDS reads and
 // MFMAs).  That pays when many experts are cold (most tiles ragged), but it puts every MFMA behind a
 // scalar branch, which costs a little when nearly all tiles are full; the launcher decides.
-template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP>
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT>
 struct Gemm {
     static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
     static constexpr int kThreads = kWaves * 64;
-    static constexpr int kTF = 256 / WT / 32;                  // 32-slot MFMA tiles per wavefront
+    static_assert(BT % (32 * WT) == 0 && BT <= kBT, "slot tile height");
+    static constexpr int kTF = BT / WT / 32;                   // 32-slot MFMA tiles per wavefront
     static constexpr int kWF = 256 / WW / 32;                  // 32-row weight MFMA tiles per wavefront
-    static constexpr int kStageRows = 256 / kWaves;            // rows of each operand a wavefront stages
+    static constexpr int kTokStageRows = BT / kWaves;          // slot rows a wavefront stages
+    static constexpr int kStageRows = 256 / kWaves;            // weight rows a wavefront stages
     static_assert(kWF % NMAT == 0, "a wavefront needs the same features of every matrix");
     static constexpr int kRowBytes = BK * 2;
-    static constexpr int kTileBytes = 256 * kRowBytes;         // one operand tile of one stage
-    static constexpr int kStageBytes = 2 * kTileBytes;         // slots + weights
+    static constexpr int kTokTileBytes = BT * kRowBytes;       // the slot tile of one stage
+    static constexpr int kTileBytes = 256 * kRowBytes;         // the weight tile of one stage
+    static constexpr int kStageBytes = kTokTileBytes + kTileBytes;  // slots, then weights
     static constexpr int kLdsBytes = STAGES * kStageBytes;
     static constexpr int kRowsPerLoad = 1024 / kRowBytes;      // rows covered by one wavefront-wide 1 KB load
-    static constexpr int kLoadsPerOperand = kStageRows / kRowsPerLoad;
-    static constexpr int kLoads = 2 * kLoadsPerOperand;        // loads per thread per stage
+    static_assert(kTokStageRows % kRowsPerLoad == 0, "whole loads per wavefront");
+    static constexpr int kLoadsTok = kTokStageRows / kRowsPerLoad;  // slot loads per thread per stage
+    static constexpr int kLoadsPerOperand = kStageRows / kRowsPerLoad;  // weight loads per thread per stage
+    static constexpr int kLoads = kLoadsTok + kLoadsPerOperand;
     static constexpr int kPieces = kRowBytes / 16;
     static constexpr int kKSteps = BK / 16;
     static constexpr int kBF = kBW / NMAT;                     // features per tile (per matrix)
@@ -198,7 +203,7 @@ struct Gemm {
                                       void* __restrict__ dst, int32_t* __restrict__ sync,
                                       float* __restrict__ scratch, unsigned char* lds) {
         const int n_ftiles = (N + kBF - 1) / kBF;
-        const int total = count_tiles(offs, E, n_ftiles);
+        const int total = count_tiles(offs, E, n_ftiles, BT);
         const int KT = K / BK;
         const int xcd = blockIdx.x % kXcds, member = blockIdx.x / kXcds;
         const int members = min((int)gridDim.x / kXcds, kMaxWgsPerXcd);
@@ -223,7 +228,7 @@ struct Gemm {
             const int t = member / p, part = member - t * p;
             const int tile_index = split ? rem_first + t : (r * kXcds + xcd) * members + t;
             int e, slot0, rows, ft;
-            tile_of(offs, E, n_ftiles, tile_index, e, slot0, rows, ft);
+            tile_of(offs, E, n_ftiles, BT, tile_index, e, slot0, rows, ft);
             const int kt0 = (int)((long)KT * part / p), kt1 = (int)((long)KT * (part + 1) / p);
             tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft, kt0, kt1, p, part,
                  scratch + ((size_t)xcd * kMaxWgsPerXcd + (size_t)t * p) * kPartialFloats,
@@ -245,45 +250,52 @@ struct Gemm {
         const int wt = wave % WT, wq = wave / WT;  // slot group, weight-row group
         const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds;
 
-        // ---- staging addresses: this wavefront stages rows [wave, wave + 1) * kStageRows of each operand
+        // ---- staging addresses: this wavefront stages rows [wave, wave + 1) * kTokStageRows of the slot tile
+        // and rows [wave, wave + 1) * kStageRows of the weight tile
         const int lrow = lane / kPieces;                       // row within a 1 KB load
         const int lpiece = lane % kPieces;                     // LDS piece position within the row
         const size_t k_first = (size_t)kt_begin * kRowBytes;   // byte offset of this piece's first K step
-        const char* gp[kLoads];
+        const char* gp[kLoads];  // slot loads first, then weight loads
 #pragma unroll
-        for (int q = 0; q < kLoadsPerOperand; ++q) {
-            const int r = wave * kStageRows + q * kRowsPerLoad + lrow;  // row in the 256-row operand tile
+        for (int q = 0; q < kLoadsTok; ++q) {
+            const int r = wave * kTokStageRows + q * kRowsPerLoad + lrow;  // row in the slot tile
             const int chunk = Swz<BK>::piece(r, lpiece);        // global piece that belongs at this position
             const int slot = slot0 + min(r, rows - 1);          // rows past the end re-read the last valid row
             const int src = (NMAT == 2) ? row_of_slot[slot] / topk : slot;
             gp[q] = reinterpret_cast<const char*>(tok_base + (size_t)src * K) + chunk * 16 + k_first;
+        }
+#pragma unroll
+        for (int q = 0; q < kLoadsPerOperand; ++q) {
+            const int r = wave * kStageRows + q * kRowsPerLoad + lrow;  // row in the 256-row weight tile
+            const int chunk = Swz<BK>::piece(r, lpiece);
             // weight rows: NMAT == 2 -> rows 0..127 are wa features, 128..255 wb features
             const int mat = (NMAT == 2) ? (r >> 7) : 0;
             const int f = min(n0 + ((NMAT == 2) ? (r & 127) : r), N - 1);
             const uint16_t* wsrc = (mat == 0) ? wa : wb;
-            gp[kLoadsPerOperand + q] = reinterpret_cast<const char*>(wsrc + ((size_t)e * N + f) * K) + chunk * 16 + k_first;
+            gp[kLoadsTok + q] = reinterpret_cast<const char*>(wsrc + ((size_t)e * N + f) * K) + chunk * 16 + k_first;
         }
         const int KT = kt_end - kt_begin;  // K steps of this piece, numbered from 0 below
-        const uint32_t stage_off_tok = (uint32_t)(wave * kStageRows * kRowBytes);
-        const uint32_t stage_off_w = (uint32_t)(kTileBytes + wave * kStageRows * kRowBytes);
+        const uint32_t stage_off_tok = (uint32_t)(wave * kTokStageRows * kRowBytes);
+        const uint32_t stage_off_w = (uint32_t)(kTokTileBytes + wave * kStageRows * kRowBytes);
 
         // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
         // computed, and within a k16 step one at a time between MFMAs (see step() below).
         // With only two stages the next K step is requested at once, in the first k16 step, so that it
         // has the whole K step to arrive; with a deeper ring the requests are spread over all k16 steps.
-        constexpr int kDmaParts = STAGES == 2 ? 1 : kKSteps;
+        constexpr int kM = kWF * kTF, kR = kWF + kTF;
+        constexpr int kDmaParts = STAGES == 2 ? (kLoads <= kM ? 1 : 2) : (kLoads % kKSteps == 0 ? kKSteps : 2);
         static_assert(kLoads % kDmaParts == 0, "loads per stage must split evenly over the k16 steps that issue them");
         constexpr int kLoadsPerPart = kLoads / kDmaParts;
         // SKIP: a wavefront whose 32 slot rows all lie past the tile's last slot stages no slot rows (the
         // fragments they would feed are skipped as well): a ragged tile then moves its weights plus only
         // its own slot rows through the load path, which is what bounds tiles of cold experts.
-        static_assert(!SKIP || kStageRows == 32, "a wavefront stages exactly one 32-slot fragment");
-        const bool stage_tok = !SKIP || wave * kStageRows < rows;
+        static_assert(32 % kTokStageRows == 0, "a wavefront stages rows of one 32-slot fragment");
+        const bool stage_tok = !SKIP || (wave * kTokStageRows) / 32 * 32 < rows;  // its fragment has valid slots
         auto dma_one = [&](int stage, int kt, int l) {
-            if (SKIP && l < kLoadsPerOperand && !stage_tok) return;
+            if (SKIP && l < kLoadsTok && !stage_tok) return;
             const uint32_t base = lds0 + (uint32_t)stage * kStageBytes;
             dma16(gp[l] + (size_t)kt * kRowBytes,
-                  base + (l < kLoadsPerOperand ? stage_off_tok : stage_off_w) + (l % kLoadsPerOperand) * 1024);
+                  base + (l < kLoadsTok ? stage_off_tok + l * 1024 : stage_off_w + (l - kLoadsTok) * 1024));
         };
 
         f32x16 acc[kWF][kTF];  // [weight frag][slot frag]
@@ -319,14 +331,13 @@ struct Gemm {
         // K step's LAST k16 step run after the next K step's barrier, paired with its first reads, so
         // the matrix pipe also has work while the wavefronts re-synchronise.
         static_assert(kKSteps % 2 == 0, "fragment buffers alternate per k16 step");
-        constexpr int kM = kWF * kTF, kR = kWF + kTF;
         static_assert(kLoadsPerPart <= kM, "a step has one slot per MFMA for its loads");
         bf16x8 tf[2][kTF], wf[2][kWF];
         auto read_one = [&](int stage, int ks, int buf, int idx) {
             const unsigned char* st = lds + stage * kStageBytes;
             if (idx < kWF)
                 wf[buf][idx] = *reinterpret_cast<const bf16x8*>(
-                    st + kTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
+                    st + kTokTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
             else if (!SKIP || idx - kWF < n_tf)
                 tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
                     st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
@@ -503,7 +514,7 @@ struct Gemm {
     }
 };
 
-template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP>
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT>
 __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uint16_t* __restrict__ tok_base,
                                                                     const uint16_t* __restrict__ wa,
                                                                     const uint16_t* __restrict__ wb,
@@ -513,7 +524,7 @@ __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uin
                                                                     int32_t* __restrict__ sync,
                                                                     float* __restrict__ scratch) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
-    Gemm<NMAT, BK, STAGES, WT, WW, SKIP>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
+    Gemm<NMAT, BK, STAGES, WT, WW, SKIP, BT>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
                                                lds_dyn);
 }
 
