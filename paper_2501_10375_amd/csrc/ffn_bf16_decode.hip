@@ -84,12 +84,6 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-// How the wavefronts of a workgroup split K (64-element steps): interleaved (wavefront w takes steps
-// w, w + 8, ...; at any moment the workgroup reads one contiguous 1 KB piece of each weight row) or
-// in contiguous runs.
-#ifndef MOE_DEC_KINTERLEAVE
-#define MOE_DEC_KINTERLEAVE 1
-#endif
 // Optional timestamps per workgroup for tuning (compiled out unless MOE_DEC_TRACE is defined).
 #ifdef MOE_DEC_TRACE
 __device__ unsigned long long g_dec_trace[512][8];
@@ -97,13 +91,8 @@ __device__ unsigned long long g_dec_trace[512][8];
 #else
 #define DEC_TRACE(slot) do { } while (0)
 #endif
-// Phase-1 tiles are dealt to the workgroups round-robin (1) or in contiguous runs (0).
-#ifndef MOE_DEC_ROT
-#define MOE_DEC_ROT 37
-#endif
-#ifndef MOE_DEC_TILE_RR
-#define MOE_DEC_TILE_RR 1
-#endif
+// How the 8 wavefronts of a workgroup split K: interleaved 64-element steps (wavefront w takes steps
+// w, w + 8, ...), so that at any moment the workgroup reads one contiguous 1 KB piece of each weight row.
 struct KSplit {
     int n_valid;     // steps of this wavefront
     int stride;      // elements between its consecutive steps
@@ -111,16 +100,9 @@ struct KSplit {
     int per;         // steps of the busiest wavefront
     __device__ KSplit(int k_steps, int wave) {
         per = (k_steps + kWaves - 1) / kWaves;
-        if (MOE_DEC_KINTERLEAVE) {
-            n_valid = wave < k_steps ? (k_steps - wave + kWaves - 1) / kWaves : 0;
-            stride = 64 * kWaves;
-            k0 = (size_t)wave * 64;
-        } else {
-            const int s_begin = wave * per;
-            n_valid = max(0, min(k_steps, s_begin + per) - s_begin);
-            stride = 64;
-            k0 = (size_t)s_begin * 64;
-        }
+        n_valid = wave < k_steps ? (k_steps - wave + kWaves - 1) / kWaves : 0;
+        stride = 64 * kWaves;
+        k0 = (size_t)wave * 64;
     }
 };
 // An expert's tokens are the columns of 16x16x32 MFMAs: NC column groups of 16 serve calls of up to
@@ -493,23 +475,19 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, uint3
     const int tiles_per_expert = F / 16;
     const int total_tiles = g.n_active * tiles_per_expert;
     // This workgroup's tiles, numbered n = 0 .. n_mine - 1 in ascending tile order.
-    const int tiles_per_wg = (total_tiles + gridDim.x - 1) / gridDim.x;
-    const int t0 = blockIdx.x * tiles_per_wg;
     // Only as many workgroups take part as are needed for the busiest one's tile count (see
     // phase1_participants()).
     // Round n deals tiles [n * g1, (n + 1) * g1) to the participants rotated by n * kRot, so that a
     // workgroup (and with it an XCD, which owns every 8th workgroup) does not always meet the same
     // residue of the tile number modulo 8, i.e. the same address bits: how fast an XCD streams
     // depends on which part of memory it reads.
-    constexpr int kRot = MOE_DEC_ROT;
+    constexpr int kRot = 37;
     const int bx = blockIdx.x;
-    const int grid = MOE_DEC_TILE_RR ? phase1_participants(total_tiles, gridDim.x) : (int)gridDim.x;  // g1
+    const int grid = phase1_participants(total_tiles, gridDim.x);  // g1
     auto slot_in_round = [&](int n) { return (bx + n * kRot) % grid; };
     const int full_rounds = grid > 0 ? total_tiles / grid : 0;
-    const int n_mine = MOE_DEC_TILE_RR
-                           ? (bx < grid ? full_rounds + (full_rounds * grid + slot_in_round(full_rounds) < total_tiles ? 1 : 0) : 0)
-                           : max(0, min(total_tiles, t0 + tiles_per_wg) - t0);
-    auto tile_id = [&](int n) { return MOE_DEC_TILE_RR ? n * grid + slot_in_round(n) : t0 + n; };
+    const int n_mine = bx < grid ? full_rounds + (full_rounds * grid + slot_in_round(full_rounds) < total_tiles ? 1 : 0) : 0;
+    auto tile_id = [&](int n) { return n * grid + slot_in_round(n); };
 
     const KSplit ks(H / 64, wave);  // ks.per <= kXSteps
     const int n_valid = ks.n_valid, kstride = ks.stride;
