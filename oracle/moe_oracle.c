@@ -30,6 +30,9 @@
  * cases, E=1 dense SwiGLU and k=E soft mixture against a library matmul,
  * homogeneity, token independence, expert-permutation equivariance, and the
  * count invariants.  No function here is "parity unpinned".
+ * tests/test_oracle_mutants.py plants mistakes in a copy of this file, one
+ * expression at a time, and requires each to fail a pin; it finds the
+ * expressions by their text, so it says so when an edit here moves them.
  */
 #include <math.h>
 #include <stddef.h>
