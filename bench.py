@@ -28,6 +28,9 @@ WORKLOADS = {
     # name: (H, F, E, k, zipf_s, prefill_T, decode_T)
     "mixtral": dict(H=4096, F=14336, E=8, k=2, zipf=1.2),
     "phi": dict(H=4096, F=6400, E=16, k=2, zipf=1.5),
+    # not a model of the paper: many small experts and top-6, to exercise the wide router and the
+    # permute / grouped GEMM with 64 groups
+    "finegrained": dict(H=2048, F=1408, E=64, k=6, zipf=0.5),
 }
 
 
