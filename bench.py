@@ -244,6 +244,13 @@ def main():
         "roofline": roofline,
     }
 
+    # ---- context for the MFMA roofline: what a register-only MFMA loop reaches on this board, with
+    # operands that never change (full clock) and with random ones (power-limited clock).  The
+    # roofline's `peak` stays the published 2.5 PFLOP/s; these two are measured, a few ms each.
+    probe = {name: moe.moe_calibrate_mfma(rnd)["tflops"] for name, rnd in (("constant_operands", False), ("random_operands", True))}
+    result["mfma_probe"] = {"unit": "TFLOP/s", **{name: round(v, 1) for name, v in probe.items()},
+                            "gemm1_frac_of_random_operand_rate": roofline["achieved"] / probe["random_operands"]}
+
     # ---- decode: a few tokens per call, weights cold (rotate over distinct weight sets) -----------
     decode = []
     if args.decode_tokens:

@@ -178,6 +178,26 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
 int moe_stage_timing_begin(int32_t max_calls);
 int moe_stage_timing_end(float* stage_ms, int32_t* stage_launches);
 
+/*
+ * Measurement aid (not part of the layer): the rate at which the device
+ * issues v_mfma_f32_32x32x16_bf16 from registers when nothing else happens,
+ * the yardstick for the grouped GEMM of the expert FFN (the paper's layer,
+ * Sec. II-A, is that dense contraction).  One workgroup of 8 wavefronts per
+ * compute unit runs `iterations` (64 .. 2^22) rounds of 8 independent MFMAs
+ * per wavefront and touches no memory in the loop.  random_operands == 0:
+ * every operand element is 1.0, the matrix cores draw little power and the
+ * loop shows the issue rate at the full clock.  random_operands != 0:
+ * operands with random signs and mantissas, as weights and activations have
+ * them, which shows what the board's power limit leaves of that rate.
+ * The kernel is launched twice on hip_stream and the second launch is timed
+ * with HIP events; the call returns after it has finished.
+ * Host outputs: *milliseconds = duration of the timed launch, *flop = its
+ * floating-point operations (2 x 32 x 32 x 16 per MFMA).
+ * Errors: MOE_ERR_SHAPE (iterations out of range, NULL output), MOE_ERR_DEVICE.
+ */
+int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds, double* flop,
+                       void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,103 @@
+// Measurement aid: the rate at which this chip issues bf16 MFMAs when nothing else happens.
+//
+// The published peak (2.5 PFLOP/s dense bf16) assumes 2.4 GHz.  Under the board's power limit the
+// clock depends on what the matrix cores multiply: operands that never change draw little power and
+// the loop below holds the full clock, operands with random mantissas and signs (what real weights
+// and activations look like) pull it down.  Timing the same register-only loop both ways gives the
+// matrix-core rate a GEMM could reach on this board if every operand were already in registers,
+// which is the yardstick the measured GEMM rates are read against.  No memory is touched in the loop.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+#include "moe_internal.h"
+
+namespace moe {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kProbeThreads = 512;       // 8 wavefronts per workgroup, one workgroup per CU: two per SIMD
+constexpr int kProbeAccumulators = 8;    // independent 32 x 32 accumulators per wavefront
+constexpr double kFlopPerMfma = 2.0 * 32 * 32 * 16;
+
+__device__ inline uint32_t mix(uint32_t v) {
+    v ^= v >> 16; v *= 0x7feb352du; v ^= v >> 15; v *= 0x846ca68bu; v ^= v >> 16;
+    return v;
+}
+// Two bf16 values of magnitude in [0.5, 2) with random sign and mantissa.
+__device__ inline uint32_t random_bf16_pair(uint32_t seed) {
+    const uint32_t h = mix(seed);
+    const uint32_t lo = 0x3f00u | (h & 0x80ffu) | ((h >> 8) & 0x0080u);
+    const uint32_t hi = 0x3f00u | ((h >> 16) & 0x80ffu) | ((h >> 24) & 0x0080u);
+    return lo | (hi << 16);
+}
+
+template <bool RANDOM>
+__global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters) {
+    f32x16 acc[kProbeAccumulators];
+    for (int a = 0; a < kProbeAccumulators; ++a)
+        for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+    bf16x8 x[4], y[4];
+    for (int n = 0; n < 4; ++n) {
+        u32x4 xv, yv;
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t seed = (blockIdx.x * (uint32_t)kProbeThreads + threadIdx.x) * 64u + n * 8u + i;
+            xv[i] = RANDOM ? random_bf16_pair(seed) : 0x3f803f80u;       // 1.0, 1.0
+            yv[i] = RANDOM ? random_bf16_pair(seed + 4u) : 0x3f803f80u;
+        }
+        x[n] = __builtin_bit_cast(bf16x8, xv);
+        y[n] = __builtin_bit_cast(bf16x8, yv);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < kProbeAccumulators; ++a)
+            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[a % 4], y[(a / 2) % 4], acc[a], 0, 0, 0);
+        if ((it & 63) == 63) {  // keep the sums finite: scale them down now and then (both flavours alike)
+#pragma unroll
+            for (int a = 0; a < kProbeAccumulators; ++a)
+                for (int r = 0; r < 16; ++r) acc[a][r] *= 0.001f;
+        }
+    }
+    float s = 0.f;
+    for (int a = 0; a < kProbeAccumulators; ++a)
+        for (int r = 0; r < 16; ++r) s += acc[a][r];
+    asm volatile("" ::"v"(s));  // the sums are the loop's only result: keep them (and with them the loop) alive
+}
+
+}  // namespace
+}  // namespace moe
+
+extern "C" int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds,
+                                  double* flop, void* hip_stream) {
+    using namespace moe;
+    if (iterations < 64 || iterations > (1 << 22) || milliseconds == nullptr || flop == nullptr) return MOE_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int grid = compute_units();
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return MOE_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return MOE_ERR_DEVICE;
+    }
+    auto launch = [&]() {
+        if (random_operands) mfma_rate_kernel<true><<<grid, kProbeThreads, 0, stream>>>(iterations);
+        else mfma_rate_kernel<false><<<grid, kProbeThreads, 0, stream>>>(iterations);
+    };
+    launch();  // the first launch also brings the clocks to where the second one finds them
+    hipError_t e = hipEventRecord(e0, stream);
+    launch();
+    if (e == hipSuccess) e = hipEventRecord(e1, stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) e = hipGetLastError();
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    *milliseconds = ms;
+    *flop = (double)grid * (kProbeThreads / 64) * (double)iterations * kProbeAccumulators * kFlopPerMfma;
+    return MOE_OK;
+}

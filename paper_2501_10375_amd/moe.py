@@ -23,7 +23,8 @@ STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTY
           -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE"}
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
-           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_stage_timing_begin", "moe_stage_timing_end")
+           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_stage_timing_begin", "moe_stage_timing_end",
+           "moe_calibrate_mfma")
 STAGES = ("route", "permute", "gemm1", "gemm2", "combine", "fused")
 
 
@@ -68,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.moe_stage_timing_begin.restype = ctypes.c_int
         L.moe_stage_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.moe_stage_timing_end.restype = ctypes.c_int
+        L.moe_calibrate_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double), vp]
+        L.moe_calibrate_mfma.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -215,6 +218,15 @@ def moe_stage_timing_end() -> dict:
     n = (ctypes.c_int32 * len(STAGES))()
     _check(lib().moe_stage_timing_end(ms, n), "moe_stage_timing_end")
     return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(STAGES)}
+
+
+def moe_calibrate_mfma(random_operands: bool, iterations: int = 20000, stream=None) -> dict:
+    """Register-only bf16 MFMA loop on every CU; returns {"ms", "flop", "tflops"} of the timed launch."""
+    ms, flop = ctypes.c_float(0.0), ctypes.c_double(0.0)
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(lib().moe_calibrate_mfma(int(bool(random_operands)), int(iterations), ctypes.byref(ms), ctypes.byref(flop),
+                                    ctypes.c_void_p(s.cuda_stream)), "moe_calibrate_mfma")
+    return {"ms": float(ms.value), "flop": float(flop.value), "tflops": float(flop.value) / (ms.value * 1e-3) / 1e12}
 
 
 class LayerOutputs:

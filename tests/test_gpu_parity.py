@@ -231,3 +231,11 @@ def test_routing_entry_points_alone(oracle):
         moe.moe_predict_next(shape, d["x"], d["wg"], d["bias"], pidx, None, None, ws)
         torch.cuda.synchronize()
         assert torch.equal(pidx, idx)
+
+
+def test_mfma_calibration_probe_is_sane():
+    """The register-only MFMA loop: plausible rates, and constant operands never slower than random ones."""
+    const = moe.moe_calibrate_mfma(False, 4096)
+    rnd = moe.moe_calibrate_mfma(True, 4096)
+    assert const["flop"] == rnd["flop"] > 0
+    assert 500 < rnd["tflops"] <= const["tflops"] * 1.05 and const["tflops"] < 2600
