@@ -100,6 +100,20 @@ def run_stack(args):
 
     st.forward(hs[0], st.new_counts())
     _, d_wall, d_gpu_ms = timed(decode_loop, L * steps)
+    # the same steps replayed from one HIP graph per step (no per-stage events inside a graph, so wall time only)
+    graph_counts = st.new_counts()
+    step = stack.CapturedStep(st, 1, graph_counts)
+    step.h_in.copy_(hs[0])
+    step.replay()
+    graph_counts.zero_()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for h in hs:
+        step.h_in.copy_(h)
+        step.replay()
+    torch.cuda.synchronize()
+    g_wall = time.perf_counter() - t0
+    graph_matches = bool(torch.equal(graph_counts, decode))
     P, D = prefill[:, :E].contiguous(), decode[:, :E].contiguous()
     sim, per = policy.daop_similarity(P, D)
     cache = policy.daop_memory_init(D, (L * E * 15) // 32)      # expert cache ratio 46.875 %
@@ -129,6 +143,9 @@ def run_stack(args):
                     "tflops_moe_gpu_time": L * T * 12.0 * H * F / (p_gpu_ms * 1e-3) / 1e12},
         "decode": {"steps": steps, "moe_gpu_ms": d_gpu_ms, "wall_ms": d_wall * 1e3,
                    "tokens_per_s_moe_gpu_time": steps / (d_gpu_ms * 1e-3), "tokens_per_s_wall": steps / d_wall,
+                   "graph_replay": {"wall_ms": g_wall * 1e3, "tokens_per_s_wall": steps / g_wall,
+                                    "GBps_wall": dec_bytes / g_wall / 1e9, "frac_of_hbm_peak_wall": dec_bytes / g_wall / 1e9 / PEAK_HBM_GBS,
+                                    "counts_equal_eager_run": graph_matches},
                    "GBps_moe_gpu_time": dec_bytes / (d_gpu_ms * 1e-3) / 1e9,
                    "frac_of_hbm_peak_moe_gpu_time": dec_bytes / (d_gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "prediction_agreement": {"prefill_exact_set_mean": exact.mean().item(), "prefill_overlap_mean": overlap.mean().item(),

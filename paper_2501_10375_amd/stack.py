@@ -77,6 +77,33 @@ class MoeStack:
         return {"h": h, "idx": self.idx[:, :T], "pred": self.pred[: self.L - 1, :T], "inputs": inputs, "outputs": outputs}
 
 
+class CapturedStep:
+    """One forward pass of a MoeStack on `tokens` tokens recorded into a HIP graph: a decode step of a
+    deep stack is a few hundred short launches, which the host cannot issue as fast as the GPU runs
+    them.  Write the hidden states into `h_in`, call replay(), read `out` (the dict forward() returns,
+    in static buffers) and `counts` (accumulated over the replays)."""
+
+    def __init__(self, st: MoeStack, tokens: int, counts: torch.Tensor):
+        self.h_in = torch.zeros((tokens, st.H), dtype=torch.float32, device=st.device)
+        self.counts = counts
+        scratch = st.new_counts()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):      # warm-up outside the capture (one-time kernel attribute calls)
+            st.forward(self.h_in, scratch)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.out = st.forward(self.h_in, counts)
+        torch.cuda.synchronize()
+        counts.zero_()      # a capture executes nothing, but leave no doubt about where the counts start
+
+    def replay(self):
+        self.graph.replay()
+        return self.out
+
+
 def agreement(pred: torch.Tensor, actual: torch.Tensor):
     """Agreement of predicted with actual expert sets.  pred [L - 1, T, k] (layer l's prediction of
     layer l + 1), actual [L, T, k].  Returns per-layer (exact-set match rate, mean overlap / k) for

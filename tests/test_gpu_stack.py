@@ -110,3 +110,24 @@ def test_precalculation_variant(oracle):
         assert np.array_equal(st_h, cache[l].cpu().numpy()[idx_h] == 0)
     print("relative error of the final hidden state vs cache slots:", errs)
     assert errs[-1] <= errs[0] + 1e-6 and errs[0] > 0
+
+
+def test_decode_step_replays_from_a_graph():
+    """The whole stack's decode step as one HIP graph: every replay equals the eager pass on the same
+    hidden state bit for bit (final hidden state, selections, predictions) and the counts add up."""
+    L, H, F, E, k = 5, 256, 512, 8, 2
+    st = stack.MoeStack(L, H, F, E, k, torch.bfloat16, DEV, zipf_s=1.2, max_tokens=4)
+    graph_counts, eager_counts = st.new_counts(), st.new_counts()
+    step = stack.CapturedStep(st, 1, graph_counts)
+    for i in range(5):
+        h = synth.normal((1, H), 7000 + i, synth.TID_X, 1.0, torch.float32, DEV)
+        ref = st.forward(h, eager_counts)                      # eager work between the replays
+        ref = {key: ref[key].clone() for key in ("h", "idx", "pred")}
+        torch.cuda.synchronize()
+        step.h_in.copy_(h)
+        got = step.replay()
+        torch.cuda.synchronize()
+        for key in ("h", "idx", "pred"):
+            assert torch.equal(got[key], ref[key]), f"replay {i}: {key}"
+        assert torch.equal(graph_counts, eager_counts), f"replay {i}: counts"
+    assert graph_counts[:, :E].sum(1).tolist() == [5 * k] * L
