@@ -168,20 +168,21 @@ __device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const sca
                 float xv0[8], xv1[8];
                 load8(x0 + h, xv0);
                 load8(x1 + h, xv1);
+                // Every load is unconditional (rows past the last expert re-read it; their sums are
+                // never looked at): a load under a branch makes the compiler wait for each one where
+                // it is used, eight memory round trips in a row instead of one.
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
-                    if (r < ne) {
-                        float wv[8];
-                        load8(wrow + (size_t)r * H + h, wv);
+                    float wv[8];
+                    load8(wrow + (size_t)min(r, ne - 1) * H + h, wv);
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            acc0[r] = fmaf(xv0[i], wv[i], acc0[r]);
-                            acc1[r] = fmaf(xv1[i], wv[i], acc1[r]);
-                        }
+                    for (int i = 0; i < 8; ++i) {
+                        acc0[r] = fmaf(xv0[i], wv[i], acc0[r]);
+                        acc1[r] = fmaf(xv1[i], wv[i], acc1[r]);
                     }
                 }
             }
-            const float v0 = reduce8_scatter(acc0, lane);
+                    const float v0 = reduce8_scatter(acc0, lane);
             const float v1 = reduce8_scatter(acc1, lane);
             if ((lane & 7) == 0) {
                 part[(wave * T + t) * 64 + eb * 8 + esub] = v0;
