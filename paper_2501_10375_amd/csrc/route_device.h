@@ -27,16 +27,42 @@ __device__ inline void load8(const uint16_t* p, float (&v)[8]) {
     }
 }
 
+// Reductions over the 64 lanes, the result in every lane.  Within a row of 16 lanes the partners
+// come through the data-parallel-primitive path (exchange with the neighbour, the neighbouring
+// pair, the mirrored half row and the mirrored row: four register-to-register moves), the four row
+// results are then read out as scalars.  An LDS-routed shuffle per step would cost about a hundred
+// cycles each, and the softmax and top-k chain some twenty of these reductions one after another.
+// Every lane performs the same operations on the same values in the same order, so all lanes hold
+// bit-identical results (the additions of wave_sum are: pairs, quads, half rows, rows, then the
+// four rows in ascending order).
+template <int CTRL>
+__device__ inline float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ inline float lane_value(float v, int lane) {  // lane is a compile-time constant at every use
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+constexpr int kDppSwapNeighbours = 0xB1;   // quad_perm [1, 0, 3, 2]
+constexpr int kDppSwapPairs = 0x4E;        // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfRowMirror = 0x141;   // lane i of each 8 <- lane 7 - i
+constexpr int kDppRowMirror = 0x140;       // lane i of each 16 <- lane 15 - i
+
 __device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
+    v = fmaxf(v, dpp_move<kDppSwapNeighbours>(v));
+    v = fmaxf(v, dpp_move<kDppSwapPairs>(v));
+    v = fmaxf(v, dpp_move<kDppHalfRowMirror>(v));
+    v = fmaxf(v, dpp_move<kDppRowMirror>(v));
+    const float r0 = lane_value(v, 0), r1 = lane_value(v, 16), r2 = lane_value(v, 32), r3 = lane_value(v, 48);
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
 __device__ inline float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v += dpp_move<kDppSwapNeighbours>(v);
+    v += dpp_move<kDppSwapPairs>(v);
+    v += dpp_move<kDppHalfRowMirror>(v);
+    v += dpp_move<kDppRowMirror>(v);
+    const float r0 = lane_value(v, 0), r1 = lane_value(v, 16), r2 = lane_value(v, 32), r3 = lane_value(v, 48);
+    return ((r0 + r1) + r2) + r3;
 }
 
 // Softmax over the E logits held one per lane (z of lane e is expert e's logit, -inf beyond E),
