@@ -264,9 +264,10 @@ def main():
     # ---- context for the MFMA roofline: what a register-only MFMA loop reaches on this board, with
     # operands that never change (full clock) and with random ones (power-limited clock).  The
     # roofline's `peak` stays the published 2.5 PFLOP/s; these two are measured, a few ms each.
-    probe = {name: moe.moe_calibrate_mfma(rnd)["tflops"] for name, rnd in (("constant_operands", False), ("random_operands", True))}
-    result["mfma_probe"] = {"unit": "TFLOP/s", **{name: round(v, 1) for name, v in probe.items()},
-                            "gemm1_frac_of_random_operand_rate": roofline["achieved"] / probe["random_operands"]}
+    probe = {name: moe.moe_calibrate_mfma(rnd) for name, rnd in (("constant_operands", False), ("random_operands", True))}
+    result["mfma_probe"] = {"unit": "TFLOP/s", **{name: round(v["tflops"], 1) for name, v in probe.items()},
+                            "shader_clock_GHz": {name: round(v["ghz"], 3) for name, v in probe.items()},
+                            "gemm1_frac_of_random_operand_rate": roofline["achieved"] / probe["random_operands"]["tflops"]}
 
     # ---- decode: a few tokens per call, weights cold (rotate over distinct weight sets) -----------
     decode = []

@@ -192,11 +192,15 @@ int moe_stage_timing_end(float* stage_ms, int32_t* stage_launches);
  * The kernel is launched twice on hip_stream and the second launch is timed
  * with HIP events; the call returns after it has finished.
  * Host outputs: *milliseconds = duration of the timed launch, *flop = its
- * floating-point operations (2 x 32 x 32 x 16 per MFMA).
+ * floating-point operations (2 x 32 x 32 x 16 per MFMA), *gigahertz (may be
+ * NULL) = the shader clock the loop ran at, from the cycle counter and the
+ * constant 100 MHz counter read by one wavefront around its loop.  Unlike
+ * the layer's entry points this call allocates (16 bytes of device memory,
+ * freed before it returns) and copies its clock readings back.
  * Errors: MOE_ERR_SHAPE (iterations out of range, NULL output), MOE_ERR_DEVICE.
  */
 int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds, double* flop,
-                       void* hip_stream);
+                       float* gigahertz, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -35,8 +35,10 @@ __device__ inline uint32_t random_bf16_pair(uint32_t seed) {
     return lo | (hi << 16);
 }
 
+// clocks[0] = shader cycles, clocks[1] = ticks of the constant 100 MHz counter that the loop of
+// workgroup 0 took (their ratio is the shader clock the loop ran at).
 template <bool RANDOM>
-__global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters) {
+__global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters, unsigned long long* clocks) {
     f32x16 acc[kProbeAccumulators];
     for (int a = 0; a < kProbeAccumulators; ++a)
         for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
@@ -51,6 +53,7 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters) {
         x[n] = __builtin_bit_cast(bf16x8, xv);
         y[n] = __builtin_bit_cast(bf16x8, yv);
     }
+    const unsigned long long c0 = __builtin_readcyclecounter(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int a = 0; a < kProbeAccumulators; ++a)
@@ -64,6 +67,12 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters) {
     float s = 0.f;
     for (int a = 0; a < kProbeAccumulators; ++a)
         for (int r = 0; r < 16; ++r) s += acc[a][r];
+    asm volatile("" ::"v"(s));  // the sums exist before the clocks are read again
+    const unsigned long long c1 = __builtin_readcyclecounter(), w1 = wall_clock64();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        clocks[0] = c1 - c0;
+        clocks[1] = w1 - w0;
+    }
     asm volatile("" ::"v"(s));  // the sums are the loop's only result: keep them (and with them the loop) alive
 }
 
@@ -71,20 +80,26 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters) {
 }  // namespace moe
 
 extern "C" int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds,
-                                  double* flop, void* hip_stream) {
+                                  double* flop, float* gigahertz, void* hip_stream) {
     using namespace moe;
     if (iterations < 64 || iterations > (1 << 22) || milliseconds == nullptr || flop == nullptr) return MOE_ERR_SHAPE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int grid = compute_units();
+    unsigned long long* clocks = nullptr;  // a calibration call may allocate: 16 bytes, freed before it returns
+    if (hipMalloc(&clocks, 2 * sizeof(unsigned long long)) != hipSuccess) return MOE_ERR_DEVICE;
     hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess) return MOE_ERR_DEVICE;
+    if (hipEventCreate(&e0) != hipSuccess) {
+        (void)hipFree(clocks);
+        return MOE_ERR_DEVICE;
+    }
     if (hipEventCreate(&e1) != hipSuccess) {
         (void)hipEventDestroy(e0);
+        (void)hipFree(clocks);
         return MOE_ERR_DEVICE;
     }
     auto launch = [&]() {
-        if (random_operands) mfma_rate_kernel<true><<<grid, kProbeThreads, 0, stream>>>(iterations);
-        else mfma_rate_kernel<false><<<grid, kProbeThreads, 0, stream>>>(iterations);
+        if (random_operands) mfma_rate_kernel<true><<<grid, kProbeThreads, 0, stream>>>(iterations, clocks);
+        else mfma_rate_kernel<false><<<grid, kProbeThreads, 0, stream>>>(iterations, clocks);
     };
     launch();  // the first launch also brings the clocks to where the second one finds them
     hipError_t e = hipEventRecord(e0, stream);
@@ -94,9 +109,13 @@ extern "C" int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, f
     float ms = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
     if (e == hipSuccess) e = hipGetLastError();
+    unsigned long long host_clocks[2] = {0, 0};
+    if (e == hipSuccess) e = hipMemcpy(host_clocks, clocks, sizeof(host_clocks), hipMemcpyDeviceToHost);
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    (void)hipFree(clocks);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
+    if (gigahertz != nullptr) *gigahertz = host_clocks[1] > 0 ? (float)((double)host_clocks[0] / (double)host_clocks[1] * 0.1) : 0.f;
     *milliseconds = ms;
     *flop = (double)grid * (kProbeThreads / 64) * (double)iterations * kProbeAccumulators * kFlopPerMfma;
     return MOE_OK;

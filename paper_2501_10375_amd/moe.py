@@ -69,7 +69,8 @@ def lib() -> ctypes.CDLL:
         L.moe_stage_timing_begin.restype = ctypes.c_int
         L.moe_stage_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.moe_stage_timing_end.restype = ctypes.c_int
-        L.moe_calibrate_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double), vp]
+        L.moe_calibrate_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(ctypes.c_float), vp]
         L.moe_calibrate_mfma.restype = ctypes.c_int
         _lib = L
     return _lib
@@ -221,12 +222,13 @@ def moe_stage_timing_end() -> dict:
 
 
 def moe_calibrate_mfma(random_operands: bool, iterations: int = 20000, stream=None) -> dict:
-    """Register-only bf16 MFMA loop on every CU; returns {"ms", "flop", "tflops"} of the timed launch."""
-    ms, flop = ctypes.c_float(0.0), ctypes.c_double(0.0)
+    """Register-only bf16 MFMA loop on every CU; returns {"ms", "flop", "tflops", "ghz"} of the timed launch."""
+    ms, flop, ghz = ctypes.c_float(0.0), ctypes.c_double(0.0), ctypes.c_float(0.0)
     s = torch.cuda.current_stream() if stream is None else stream
     _check(lib().moe_calibrate_mfma(int(bool(random_operands)), int(iterations), ctypes.byref(ms), ctypes.byref(flop),
-                                    ctypes.c_void_p(s.cuda_stream)), "moe_calibrate_mfma")
-    return {"ms": float(ms.value), "flop": float(flop.value), "tflops": float(flop.value) / (ms.value * 1e-3) / 1e12}
+                                    ctypes.byref(ghz), ctypes.c_void_p(s.cuda_stream)), "moe_calibrate_mfma")
+    return {"ms": float(ms.value), "flop": float(flop.value), "tflops": float(flop.value) / (ms.value * 1e-3) / 1e12,
+            "ghz": float(ghz.value)}
 
 
 class LayerOutputs:

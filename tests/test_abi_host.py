@@ -192,8 +192,8 @@ def test_product_code_never_touches_the_oracle():
 def test_calibration_call_validates_on_the_host(L):
     ms, flop = ctypes.c_float(0), ctypes.c_double(0)
     L.moe_calibrate_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_float),
-                                     ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
     L.moe_calibrate_mfma.restype = ctypes.c_int
-    assert L.moe_calibrate_mfma(1, 8, ctypes.byref(ms), ctypes.byref(flop), None) == -2       # too few iterations (MOE_ERR_SHAPE)
-    assert L.moe_calibrate_mfma(1, 1 << 23, ctypes.byref(ms), ctypes.byref(flop), None) == -2  # too many
-    assert L.moe_calibrate_mfma(0, 4096, None, ctypes.byref(flop), None) == -2                 # NULL output
+    assert L.moe_calibrate_mfma(1, 8, ctypes.byref(ms), ctypes.byref(flop), None, None) == -2       # too few iterations (MOE_ERR_SHAPE)
+    assert L.moe_calibrate_mfma(1, 1 << 23, ctypes.byref(ms), ctypes.byref(flop), None, None) == -2  # too many
+    assert L.moe_calibrate_mfma(0, 4096, None, ctypes.byref(flop), None, None) == -2                 # NULL output

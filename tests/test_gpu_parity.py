@@ -239,3 +239,4 @@ def test_mfma_calibration_probe_is_sane():
     rnd = moe.moe_calibrate_mfma(True, 4096)
     assert const["flop"] == rnd["flop"] > 0
     assert 500 < rnd["tflops"] <= const["tflops"] * 1.05 and const["tflops"] < 2600
+    assert 0.5 < rnd["ghz"] <= const["ghz"] * 1.05 and const["ghz"] < 2.6
