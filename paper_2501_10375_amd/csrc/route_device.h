@@ -27,6 +27,36 @@ __device__ inline void load8(const uint16_t* p, float (&v)[8]) {
     }
 }
 
+// Eight consecutive elements as loaded (16 or 32 bytes), converted to fp32 only when they are used,
+// so that a group of loads can be issued back to back before the first conversion.
+template <typename scalar_t>
+struct Raw8;
+template <>
+struct Raw8<float> {
+    float4 a, b;
+    __device__ inline void load(const float* p) {
+        a = *reinterpret_cast<const float4*>(p);
+        b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ inline void get(float (&v)[8]) const {
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+};
+template <>
+struct Raw8<uint16_t> {
+    uint4 q;
+    __device__ inline void load(const uint16_t* p) { q = *reinterpret_cast<const uint4*>(p); }
+    __device__ inline void get(float (&v)[8]) const {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
 // Reductions over the 64 lanes, the result in every lane.  Within a row of 16 lanes the partners
 // come through the data-parallel-primitive path (exchange with the neighbour, the neighbouring
 // pair, the mirrored half row and the mirrored row: four register-to-register moves), the four row
@@ -191,16 +221,23 @@ __device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const sca
 #pragma unroll
             for (int r = 0; r < 8; ++r) acc0[r] = acc1[r] = 0.f;
             for (int h = (wave * 64 + lane) * 8; h < H; h += 8 * 512) {
+                // All loads of the step first, unconditionally (rows past the last expert re-read it;
+                // their sums are never looked at), and nothing else scheduled between them: a load
+                // under a branch, or one the scheduler leaves next to its use, costs a memory round
+                // trip of its own, ten in a row instead of one.
+                Raw8<scalar_t> xr0, xr1, wr[8];
+                xr0.load(x0 + h);
+                xr1.load(x1 + h);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) wr[r].load(wrow + (size_t)min(r, ne - 1) * H + h);
+                __builtin_amdgcn_sched_barrier(0);
                 float xv0[8], xv1[8];
-                load8(x0 + h, xv0);
-                load8(x1 + h, xv1);
-                // Every load is unconditional (rows past the last expert re-read it; their sums are
-                // never looked at): a load under a branch makes the compiler wait for each one where
-                // it is used, eight memory round trips in a row instead of one.
+                xr0.get(xv0);
+                xr1.get(xv1);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
                     float wv[8];
-                    load8(wrow + (size_t)min(r, ne - 1) * H + h, wv);
+                    wr[r].get(wv);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         acc0[r] = fmaf(xv0[i], wv[i], acc0[r]);
@@ -208,7 +245,7 @@ __device__ inline void route_tokens_wg(const scalar_t* __restrict__ x, const sca
                     }
                 }
             }
-                    const float v0 = reduce8_scatter(acc0, lane);
+            const float v0 = reduce8_scatter(acc0, lane);
             const float v1 = reduce8_scatter(acc1, lane);
             if ((lane & 7) == 0) {
                 part[(wave * T + t) * 64 + eb * 8 + esub] = v0;
