@@ -313,6 +313,12 @@ def main():
             })
         del layers
     result["decode"] = decode
+    # ---- context for the HBM roofline: a plain read stream over one weight tensor of the layer (0.94 GB for the
+    # Mixtral shape).  The roofline's `peak` stays the published 8 TB/s; this one is measured.
+    stream_probe = moe.moe_calibrate_read_stream(d["w1"])
+    result["hbm_probe"] = {"unit": "GB/s", "read_stream": round(stream_probe["GBps"], 1), "bytes": stream_probe["bytes"]}
+    if decode:
+        result["hbm_probe"]["decode_frac_of_read_stream"] = decode[0]["roofline"]["achieved"] / stream_probe["GBps"]
 
     # ---- the CPU oracle on this machine's host cores, on a bounded sample of the headline workload ----
     if not args.no_cpu_baseline:

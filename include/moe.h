@@ -202,6 +202,25 @@ int moe_stage_timing_end(float* stage_ms, int32_t* stage_launches);
 int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds, double* flop,
                        float* gigahertz, void* hip_stream);
 
+/*
+ * Measurement aid (not part of the layer): the rate of a plain read stream
+ * out of device memory, the yardstick for decode-size calls, which are bound
+ * by reading each selected expert's weights once (the paper's Table I and
+ * Sec. III-A: expert parameters dwarf the activations).  One workgroup per
+ * compute unit reads its contiguous share of device_buffer (device memory,
+ * 16-byte aligned, read only; `bytes` is rounded down to a whole number of
+ * rounds of all workgroups, 16 KB each) with 16-byte loads and keeps nothing.
+ * The buffer should be much larger than the 256 MB memory-side cache (a
+ * layer's expert weights are).  The kernel is launched twice on hip_stream
+ * and the second launch is timed with HIP events; the call returns after it
+ * has finished and allocates nothing.
+ * Host outputs: *milliseconds, *bytes_read = bytes the timed launch read.
+ * Errors: MOE_ERR_NULL, MOE_ERR_ALIGN, MOE_ERR_SHAPE (buffer smaller than one
+ * round), MOE_ERR_DEVICE.
+ */
+int moe_calibrate_read_stream(const void* device_buffer, size_t bytes, float* milliseconds, double* bytes_read,
+                              void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

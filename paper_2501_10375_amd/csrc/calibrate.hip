@@ -76,8 +76,60 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters, uns
     asm volatile("" ::"v"(s));  // the sums are the loop's only result: keep them (and with them the loop) alive
 }
 
+// Plain read stream: every workgroup reads its contiguous share of the buffer with 16-byte loads,
+// consecutive lanes on consecutive addresses, eight loads (8 KB per workgroup) in flight per
+// wavefront, and keeps nothing.  What this reaches is what a kernel that only has to pull bytes out
+// of HBM gets on this device, the yardstick for the decode-size calls of the layer.
+constexpr int kStreamUnroll = 8;
+__global__ __launch_bounds__(kProbeThreads) void read_stream_kernel(const u32x4* __restrict__ data, size_t n16) {
+    const size_t per_wg = n16 / gridDim.x;  // 16-byte pieces of this workgroup (the host passes a multiple)
+    const u32x4* mine = data + (size_t)blockIdx.x * per_wg;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (size_t i = threadIdx.x; i < per_wg; i += (size_t)kProbeThreads * kStreamUnroll) {
+        u32x4 v[kStreamUnroll];
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) v[u] = mine[min(i + (size_t)u * kProbeThreads, per_wg - 1)];
+#pragma unroll
+        for (int u = 0; u < kStreamUnroll; ++u) acc ^= v[u];
+    }
+    asm volatile("" ::"v"(acc));  // the loads are the point
+}
+
 }  // namespace
 }  // namespace moe
+
+extern "C" int moe_calibrate_read_stream(const void* device_buffer, size_t bytes, float* milliseconds,
+                                         double* bytes_read, void* hip_stream) {
+    using namespace moe;
+    if (device_buffer == nullptr || milliseconds == nullptr || bytes_read == nullptr) return MOE_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(device_buffer) & 15u) != 0) return MOE_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int grid = compute_units();
+    const size_t unit = (size_t)grid * kProbeThreads * kStreamUnroll * 16;  // one round of every workgroup
+    const size_t n16 = bytes / unit * (unit / 16);
+    if (n16 == 0) return MOE_ERR_SHAPE;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return MOE_ERR_DEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return MOE_ERR_DEVICE;
+    }
+    const u32x4* data = static_cast<const u32x4*>(device_buffer);
+    read_stream_kernel<<<grid, kProbeThreads, 0, stream>>>(data, n16);
+    hipError_t e = hipEventRecord(e0, stream);
+    read_stream_kernel<<<grid, kProbeThreads, 0, stream>>>(data, n16);
+    if (e == hipSuccess) e = hipEventRecord(e1, stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) e = hipGetLastError();
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    *milliseconds = ms;
+    *bytes_read = (double)n16 * 16.0;
+    return MOE_OK;
+}
 
 extern "C" int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds,
                                   double* flop, float* gigahertz, void* hip_stream) {

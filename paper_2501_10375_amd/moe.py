@@ -24,7 +24,7 @@ STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTY
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
            "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_stage_timing_begin", "moe_stage_timing_end",
-           "moe_calibrate_mfma")
+           "moe_calibrate_mfma", "moe_calibrate_read_stream")
 STAGES = ("route", "permute", "gemm1", "gemm2", "combine", "fused")
 
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.moe_calibrate_mfma.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double),
                                          ctypes.POINTER(ctypes.c_float), vp]
         L.moe_calibrate_mfma.restype = ctypes.c_int
+        L.moe_calibrate_read_stream.argtypes = [vp, sz, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double), vp]
+        L.moe_calibrate_read_stream.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -229,6 +231,17 @@ def moe_calibrate_mfma(random_operands: bool, iterations: int = 20000, stream=No
                                     ctypes.byref(ghz), ctypes.c_void_p(s.cuda_stream)), "moe_calibrate_mfma")
     return {"ms": float(ms.value), "flop": float(flop.value), "tflops": float(flop.value) / (ms.value * 1e-3) / 1e12,
             "ghz": float(ghz.value)}
+
+
+def moe_calibrate_read_stream(buffer: torch.Tensor, stream=None) -> dict:
+    """Plain read stream over a device tensor; returns {"ms", "bytes", "GBps"} of the timed launch."""
+    assert buffer.is_cuda and buffer.is_contiguous()
+    ms, nbytes = ctypes.c_float(0.0), ctypes.c_double(0.0)
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(lib().moe_calibrate_read_stream(ctypes.c_void_p(buffer.data_ptr()), buffer.numel() * buffer.element_size(),
+                                           ctypes.byref(ms), ctypes.byref(nbytes), ctypes.c_void_p(s.cuda_stream)),
+           "moe_calibrate_read_stream")
+    return {"ms": float(ms.value), "bytes": float(nbytes.value), "GBps": float(nbytes.value) / (ms.value * 1e-3) / 1e9}
 
 
 class LayerOutputs:

@@ -197,3 +197,13 @@ def test_calibration_call_validates_on_the_host(L):
     assert L.moe_calibrate_mfma(1, 8, ctypes.byref(ms), ctypes.byref(flop), None, None) == -2       # too few iterations (MOE_ERR_SHAPE)
     assert L.moe_calibrate_mfma(1, 1 << 23, ctypes.byref(ms), ctypes.byref(flop), None, None) == -2  # too many
     assert L.moe_calibrate_mfma(0, 4096, None, ctypes.byref(flop), None, None) == -2                 # NULL output
+
+
+def test_read_stream_call_validates_on_the_host(L):
+    ms, nbytes = ctypes.c_float(0), ctypes.c_double(0)
+    L.moe_calibrate_read_stream.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_float),
+                                            ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    L.moe_calibrate_read_stream.restype = ctypes.c_int
+    assert L.moe_calibrate_read_stream(None, 1 << 30, ctypes.byref(ms), ctypes.byref(nbytes), None) == -1      # NULL buffer
+    assert L.moe_calibrate_read_stream(ctypes.c_void_p(4096), 1 << 30, None, ctypes.byref(nbytes), None) == -1  # NULL output
+    assert L.moe_calibrate_read_stream(ctypes.c_void_p(4100), 1 << 30, ctypes.byref(ms), ctypes.byref(nbytes), None) == -5  # alignment

@@ -240,3 +240,11 @@ def test_mfma_calibration_probe_is_sane():
     assert const["flop"] == rnd["flop"] > 0
     assert 500 < rnd["tflops"] <= const["tflops"] * 1.05 and const["tflops"] < 2600
     assert 0.5 < rnd["ghz"] <= const["ghz"] * 1.05 and const["ghz"] < 2.6
+
+
+def test_read_stream_probe_is_sane():
+    """The plain read stream: a plausible rate, and the bytes it reports are what it was given (rounded down)."""
+    buf = torch.empty(1 << 29, dtype=torch.uint8, device=DEV).fill_(1)     # 512 MB
+    r = moe.moe_calibrate_read_stream(buf)
+    assert 0.9 * buf.numel() <= r["bytes"] <= buf.numel()
+    assert 1000 < r["GBps"] < 8000
