@@ -4,7 +4,7 @@
 A "step" is one moe_layer call (routing, counts, next-layer prediction, permute, grouped SwiGLU
 experts, combine) on one batch of synthetic input that is already resident in HBM.  The headline
 workload is the Mixtral-8x7B-shaped layer (Table III of the DAOP paper: hidden 4096, 8 experts of
-FFN width 14336, top-2) at a 4096-token prefill; the same run also times single-token decode and
+FFN width 14336, top-2) at a 4096-token prefill; the same run also times decode calls of 1, 8 and 32 tokens and
 the CPU oracle on the host cores.  One JSON line is printed.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--model", default="mixtral", choices=sorted(WORKLOADS))
     ap.add_argument("--tokens", type=int, default=4096, help="tokens of the headline (prefill) workload")
-    ap.add_argument("--decode-tokens", type=int, nargs="*", default=[1], help="decode batch sizes also timed")
+    ap.add_argument("--decode-tokens", type=int, nargs="*", default=[1, 8, 32], help="decode batch sizes also timed")
     ap.add_argument("--decode-layers", type=int, default=4,
                     help="distinct weight sets the decode loop rotates over (keeps the weights cold in cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
