@@ -1,6 +1,6 @@
 """Helpers that compare the HIP library with the CPU oracle on the same seeded inputs.
 
-Rules (fixed by the benchmark spec, restated in the design doc):
+Rules:
   * selected experts and activation counts must match the oracle bit-exactly, leaving out only
     tokens whose oracle top-k margin (smallest deciding gap of the fp32 probabilities) is below
     1e-4; those are counted and returned;
