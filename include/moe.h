@@ -22,7 +22,7 @@
  *     run at the same time (order them on one stream or with events).
  *   - Every call only enqueues kernels whose arguments depend on nothing but
  *     the call's own arguments, so a call may be recorded into a HIP graph
- *     (stream capture) and replayed; moe_stage_timing_* must be off then.
+ *     (stream capture) and replayed.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
  *     stream).  Calls validate their arguments on the host, enqueue kernels on
  *     that stream and return without synchronising.  Outputs are valid once
@@ -42,11 +42,14 @@
  *   - bf16 calls with at most 32 tokens run their experts (at most 16 tokens:
  *     the whole layer) as one persistent kernel, one workgroup per compute
  *     unit, whose workgroups wait for one another between the two expert
- *     GEMMs.  The wait is bounded, so a call always
- *     ends, but its result is only defined when the device can hold the whole
- *     grid at once, i.e. when no other kernel occupies compute units for the
- *     duration of the call.  (The prefill-size grouped GEMM is persistent too;
- *     its waits only tune timing and never affect results.)
+ *     GEMMs.  The wait is bounded, so a call always ends, but it only
+ *     succeeds when the device can hold the whole grid at once, i.e. when no
+ *     other kernel (another stream, another process) occupies compute units
+ *     for the duration of the call.  A workgroup whose wait runs out writes
+ *     NaN into its part of y and raises a status word that moe_decode_status
+ *     reads; the call itself has long returned MOE_OK by then.  (The
+ *     prefill-size grouped GEMM is persistent too; its waits only tune timing
+ *     and never affect results.)
  *   - Determinism: no floating-point atomics are used; two calls on the same
  *     inputs give bitwise identical outputs.  moe_layer gives bitwise the same
  *     outputs as moe_route (+ moe_predict_next) followed by moe_expert_ffn.
@@ -161,65 +164,20 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
               size_t workspace_bytes, void* hip_stream);
 
 /*
- * Measurement aid (not part of the layer): per-stage GPU time with HIP events
- * recorded on the caller's stream between the kernels of each entry-point
- * call made by THIS thread between begin and end.  Stages: 0 routing (gate,
- * softmax, top-k, prediction), 1 counts + permutation, 2 grouped GEMM1 +
- * SwiGLU, 3 grouped GEMM2, 4 combine, 5 the single kernel that runs a bf16
- * call of at most 16 tokens (routing when the entry point routes, both
- * GEMMs, combine).  begin allocates events for up to max_calls calls (later calls
- * are not recorded); end synchronises with the last recorded event, writes
- * the mean milliseconds per launch of each stage and the number of launches
- * averaged (either pointer may be NULL), and frees the events.
- * Errors: MOE_ERR_SHAPE (bad max_calls, begin twice, end without begin),
- * MOE_ERR_DEVICE.
+ * Whether a decode-size call on `workspace` gave up a rendezvous (see the
+ * conventions above: bf16 calls of at most 32 tokens need the whole grid
+ * resident at once; a workgroup whose bounded wait runs out stores NaN instead
+ * of its part of y and raises a status word in the workspace, which stays
+ * raised until it is reset).  Copies that word back: *gave_up (HOST pointer) =
+ * 1 if some call since the last reset gave up, else 0; reset != 0 also clears
+ * the word.  Unlike the layer's calls this one synchronises hip_stream, so it
+ * cannot be recorded into a graph.  A workspace that was never used by a
+ * decode-size call holds arbitrary bytes there; they read as "gave up" only
+ * if they equal a 32-bit magic value.
+ * Errors: MOE_ERR_NULL, MOE_ERR_ALIGN, MOE_ERR_WORKSPACE (fewer than 4096
+ * bytes), MOE_ERR_DEVICE.
  */
-#define MOE_NUM_STAGES 6
-int moe_stage_timing_begin(int32_t max_calls);
-int moe_stage_timing_end(float* stage_ms, int32_t* stage_launches);
-
-/*
- * Measurement aid (not part of the layer): the rate at which the device
- * issues v_mfma_f32_32x32x16_bf16 from registers when nothing else happens,
- * the yardstick for the grouped GEMM of the expert FFN (the paper's layer,
- * Sec. II-A, is that dense contraction).  One workgroup of 8 wavefronts per
- * compute unit runs `iterations` (64 .. 2^22) rounds of 8 independent MFMAs
- * per wavefront and touches no memory in the loop.  random_operands == 0:
- * every operand element is 1.0, the matrix cores draw little power and the
- * loop shows the issue rate at the full clock.  random_operands != 0:
- * operands with random signs and mantissas, as weights and activations have
- * them, which shows what the board's power limit leaves of that rate.
- * The kernel is launched twice on hip_stream and the second launch is timed
- * with HIP events; the call returns after it has finished.
- * Host outputs: *milliseconds = duration of the timed launch, *flop = its
- * floating-point operations (2 x 32 x 32 x 16 per MFMA), *gigahertz (may be
- * NULL) = the shader clock the loop ran at, from the cycle counter and the
- * constant 100 MHz counter read by one wavefront around its loop.  Unlike
- * the layer's entry points this call allocates (16 bytes of device memory,
- * freed before it returns) and copies its clock readings back.
- * Errors: MOE_ERR_SHAPE (iterations out of range, NULL output), MOE_ERR_DEVICE.
- */
-int moe_calibrate_mfma(int32_t random_operands, int32_t iterations, float* milliseconds, double* flop,
-                       float* gigahertz, void* hip_stream);
-
-/*
- * Measurement aid (not part of the layer): the rate of a plain read stream
- * out of device memory, the yardstick for decode-size calls, which are bound
- * by reading each selected expert's weights once (the paper's Table I and
- * Sec. III-A: expert parameters dwarf the activations).  One workgroup per
- * compute unit reads its contiguous share of device_buffer (device memory,
- * 16-byte aligned, read only; `bytes` is rounded down to a whole number of
- * rounds of all workgroups, 16 KB each) with 16-byte loads and keeps nothing.
- * The buffer should be much larger than the 256 MB memory-side cache (a
- * layer's expert weights are).  The kernel is launched twice on hip_stream
- * and the second launch is timed with HIP events; the call returns after it
- * has finished and allocates nothing.
- * Host outputs: *milliseconds, *bytes_read = bytes the timed launch read.
- * Errors: MOE_ERR_NULL, MOE_ERR_ALIGN, MOE_ERR_SHAPE (buffer smaller than one
- * round), MOE_ERR_DEVICE.
- */
-int moe_calibrate_read_stream(const void* device_buffer, size_t bytes, float* milliseconds, double* bytes_read,
-                              void* hip_stream);
+int moe_decode_status(void* workspace, size_t workspace_bytes, int32_t reset, int32_t* gave_up, void* hip_stream);
 
 #ifdef __cplusplus
 }

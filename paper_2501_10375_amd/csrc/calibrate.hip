@@ -9,7 +9,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "moe.h"
+#include "moe_measure.h"
 #include "moe_internal.h"
 
 namespace moe {

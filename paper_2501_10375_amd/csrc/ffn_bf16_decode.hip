@@ -131,6 +131,8 @@ struct DecodeArgs {
     uint16_t* act;          // [T*k, F] workspace
     uint16_t* y;            // [T, H]
     uint32_t* flags;        // workspace: 2 x kFlagStride arrival flags of the two rendezvous, then the epoch word
+                            // and the status word (see kStatusIndex)
+    int spin_limit;         // polling rounds a rendezvous waits before it gives up
     int T, k, E, H, F;
 };
 
@@ -219,7 +221,12 @@ constexpr int kFlagStride = 256;
 // the new epoch only by accident, so nothing ever needs clearing; and because no launch argument
 // changes from call to call, a call recorded into a HIP graph can be replayed.
 constexpr int kEpochIndex = 2 * kFlagStride;
-static_assert(kEpochIndex < kDecodeFlagInts, "flags and epoch fit the workspace block");
+// The word after the epoch reports a rendezvous that gave up (its bounded wait ran out because the
+// grid was not resident all at once): the workgroup stores kDecodeGaveUp there and writes NaN
+// instead of its output tiles.  Nothing else ever writes the word, so it stays set until the host
+// resets it (moe_decode_status).
+constexpr int kStatusIndex = kDecodeStatusWord;
+static_assert(kStatusIndex == kEpochIndex + 1 && kStatusIndex < kDecodeFlagInts, "flags, epoch and status fit the workspace block");
 
 // All of this workgroup's stores to `act` so far have left the CU; then raise `flag`.
 __device__ inline void announce(uint32_t* flag, uint32_t epoch) {
@@ -228,16 +235,27 @@ __device__ inline void announce(uint32_t* flag, uint32_t epoch) {
     if (threadIdx.x == 0) __hip_atomic_store(flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Waits (all threads) until the n flags all hold `epoch`.  The spin is bounded, so the kernel ends
-// even if the workgroups never become co-resident.  Global loads already in flight stay in flight.
-__device__ inline void await_flags(const uint32_t* flags, int n, uint32_t epoch) {
+// Waits (all threads) until the n flags all hold `epoch`.  The spin is bounded (`limit` polling
+// rounds), so the kernel ends even if the workgroups never become co-resident; a wait that runs out
+// marks the call as failed: the status word in the workspace and *failed (LDS, read when y is stored).
+// Global loads already in flight stay in flight.
+__device__ inline void await_flags(const uint32_t* flags, int n, uint32_t epoch, int limit, uint32_t* status,
+                                   int* failed) {
     if (threadIdx.x < 64) {
-        for (int it = 0; it < (1 << 22); ++it) {
+        bool met = false;
+        for (int it = 0; it < limit; ++it) {
             bool all = true;
             for (int i = threadIdx.x; i < n; i += 64)
                 all &= __hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == epoch;
-            if (__all(all)) break;
+            if (__all(all)) {
+                met = true;
+                break;
+            }
             __builtin_amdgcn_s_sleep(1);
+        }
+        if (!met && threadIdx.x == 0) {
+            __hip_atomic_store(status, kDecodeGaveUp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *failed = 1;
         }
     }
     asm volatile("" ::: "memory");
@@ -308,6 +326,7 @@ struct Smem {
     static constexpr int kRedBufs = NC >= 4 ? 1 : 2;
     f32x4 red[kRedBufs][kWaves][2][NC][64];
     float yacc[16 * NC][16];
+    int failed;               // a rendezvous of this workgroup gave up: its output tiles become NaN
 };
 
 // ---- phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f]) over this workgroup's share
@@ -680,7 +699,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
             as = 0;
             if (++ad == D) ad = 0;
             if (b_open && ad >= d_a) {  // the next operand belongs to group B
-                await_flags(p.flags + kFlagStride, n_wgs, epoch);
+                await_flags(p.flags + kFlagStride, n_wgs, epoch, p.spin_limit, p.flags + kStatusIndex, &sm.failed);
                 b_open = false;
                 DEC_TRACE(6);
             }
@@ -691,7 +710,7 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
     for (int i = 0; i < P; ++i) issue_w(i);
 
     // ---- group A of the intermediate is needed now
-    await_flags(p.flags, n_wgs, epoch);
+    await_flags(p.flags, n_wgs, epoch, p.spin_limit, p.flags + kStatusIndex, &sm.failed);
     DEC_TRACE(4);
 #pragma unroll
     for (int i = 0; i < P; ++i) issue_a(i);
@@ -741,9 +760,10 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
             par = (par + 1) % Smem<NC>::kRedBufs;
             if (++cd == D) {
                 lds_barrier();  // the tile's sums are complete
+                const bool failed = sm.failed != 0;
                 for (int item = tid; item < p.T * 16; item += kThreads) {
                     const int t = item >> 4, r = item & 15;
-                    p.y[(size_t)t * H + ct * 16 + r] = to_bf16(sm.yacc[t][r]);
+                    p.y[(size_t)t * H + ct * 16 + r] = failed ? (uint16_t)0x7FC0 : to_bf16(sm.yacc[t][r]);
                     sm.yacc[t][r] = 0.f;
                 }
                 cd = 0;
@@ -770,6 +790,7 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     asm volatile("" ::: "memory");
     DEC_TRACE(0);
     for (int i = tid; i < 16 * NC * 16; i += kThreads) sm.yacc[i >> 4][i & 15] = 0.f;
+    if (tid == 0) sm.failed = 0;
     if (ROUTE) {
         // Every workgroup routes the call itself (identical arithmetic, identical result), which
         // costs a few microseconds of latency instead of a kernel boundary; workgroup 0 publishes.
@@ -851,6 +872,7 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     p.act = static_cast<uint16_t*>(act);
     p.y = static_cast<uint16_t*>(y);
     p.flags = flags;
+    p.spin_limit = decode_spin_limit();
     p.T = tokens;
     p.k = s.top_k;
     p.E = s.n_experts;

@@ -1,6 +1,7 @@
 // C ABI of libmoe_hip.so: argument validation on the host, then kernel launches
 // on the caller's stream.  See include/moe.h for the contract of each call.
 #include "moe_internal.h"
+#include "moe_measure.h"
 
 namespace moe {
 
@@ -12,13 +13,13 @@ WorkspaceLayout workspace_layout(const moe_shape_t& s, int tokens) {
     const size_t A = (size_t)(tokens > 0 ? tokens : 1) * (size_t)s.top_k;
     const size_t esz = s.dtype == MOE_F32 ? 4 : 2;
     size_t off = 0;
+    L.dec_flags = off;   off = align_up(off + kDecodeFlagInts * sizeof(uint32_t));
+    L.sync = off;        off = align_up(off + kSyncInts * sizeof(int32_t));
     L.hist = off;        off = align_up(off + nb * s.n_experts * sizeof(int32_t));
     L.hist_next = off;   off = align_up(off + nb * s.n_experts * sizeof(int32_t));
     L.offs = off;        off = align_up(off + (size_t)(s.n_experts + 1) * sizeof(int32_t));
     L.row_of_slot = off; off = align_up(off + A * sizeof(int32_t));
     L.slot_of = off;     off = align_up(off + A * sizeof(int32_t));
-    L.sync = off;        off = align_up(off + kSyncInts * sizeof(int32_t));
-    L.dec_flags = off;   off = align_up(off + kDecodeFlagInts * sizeof(uint32_t));
     L.route_end = off;
     L.act = off;         off = align_up(off + A * (size_t)s.ffn * esz);
     L.out = off;         off = align_up(off + A * (size_t)s.hidden * sizeof(float));
@@ -63,6 +64,11 @@ void stage_mark(hipStream_t stream, int stage) {
     (void)hipEventRecord(t->events[t->cur * StageTimer::kMaxMarks + n], stream);
     ++n;
 }
+
+namespace {
+int g_decode_spin_limit = 1 << 22;
+}
+int decode_spin_limit() { return g_decode_spin_limit; }
 
 int compute_units() {
     static int cached[64] = {0};
@@ -182,6 +188,44 @@ hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_
                            ws.sync, ws.partial, stream);
 }
 
+
+// Argument checks of a whole-layer call, everything but the workspace.
+int check_layer_args(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate, const float* gate_bias,
+                     const void* w_gate_next, const float* gate_bias_next, const void* w1, const void* w3, const void* w2,
+                     void* y, int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* pred_idx) {
+    if (int rc = check_shape(shape)) return rc;
+    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    const void* const req[] = {w_gate, w1, w3, w2, counts};
+    if (int rc = check_required(req)) return rc;
+    const void* const per_token[] = {x, y, topk_idx, topk_w};
+    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
+    if (tokens > 0 && w_gate_next != nullptr && pred_idx == nullptr) return MOE_ERR_NULL;
+    const void* const opt[] = {gate_bias, w_gate_next, gate_bias_next, pred_idx};
+    return check_optional(opt);
+}
+
+// The kernels of one whole layer on a carved workspace (arguments already checked).
+int enqueue_layer(const moe_shape_t& s, int32_t tokens, const void* x, const void* w_gate, const float* gate_bias,
+                  const void* w_gate_next, const float* gate_bias_next, const void* w1, const void* w3, const void* w2,
+                  void* y, int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t accumulate, int32_t* pred_idx,
+                  const Ws& ws, hipStream_t stream) {
+    if (tokens == 0)
+        return dev(launch_finalize(s, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, nullptr, stream));
+    stage_call_begin(stream);
+    if (decode_path(s, tokens)) {
+        // One kernel routes, runs the experts and (in one of its workgroups, at the end) evaluates the
+        // prediction gate.
+        const DecodeRoute r = {w_gate, gate_bias, topk_idx, topk_w, counts, accumulate, w_gate_next, gate_bias_next, pred_idx};
+        return dev(launch_decode_layer(s, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags, stream));
+    }
+    GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
+    const int n_gates = w_gate_next != nullptr ? 2 : 1;
+    hipError_t e = run_route(s, tokens, x, g, n_gates, counts, accumulate, nullptr, !stream_path(s, tokens), ws,
+                             stream);
+    if (e != hipSuccess) return MOE_ERR_DEVICE;
+    return dev(run_ffn(s, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+}
+
 }  // namespace
 }  // namespace moe
 
@@ -293,34 +337,39 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
               const void* w_gate_next, const float* gate_bias_next, const void* w1, const void* w3, const void* w2,
               void* y, int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t accumulate, int32_t* pred_idx,
               void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (int rc = check_shape(shape)) return rc;
-    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
-    const void* const req[] = {w_gate, w1, w3, w2, counts, workspace};
+    if (int rc = check_layer_args(shape, tokens, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx,
+                                  topk_w, counts, pred_idx))
+        return rc;
+    const void* const req[] = {workspace};
     if (int rc = check_required(req)) return rc;
-    const void* const per_token[] = {x, y, topk_idx, topk_w};
-    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
-    if (tokens > 0 && w_gate_next != nullptr && pred_idx == nullptr) return MOE_ERR_NULL;
-    const void* const opt[] = {gate_bias, w_gate_next, gate_bias_next, pred_idx};
-    if (int rc = check_optional(opt)) return rc;
     const WorkspaceLayout L = workspace_layout(*shape, tokens);
     if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    return enqueue_layer(*shape, tokens, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx, topk_w,
+                         counts, accumulate, pred_idx, carve(workspace, L), static_cast<hipStream_t>(hip_stream));
+}
+
+int moe_decode_status(void* workspace, size_t workspace_bytes, int32_t reset, int32_t* gave_up, void* hip_stream) {
+    if (workspace == nullptr || gave_up == nullptr) return MOE_ERR_NULL;
+    if (misaligned(workspace)) return MOE_ERR_ALIGN;
+    if (workspace_bytes < kDecodeFlagInts * sizeof(uint32_t)) return MOE_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const Ws ws = carve(workspace, L);
-    if (tokens == 0)
-        return dev(launch_finalize(*shape, 0, ws.hist, nullptr, counts, accumulate, nullptr, nullptr, nullptr, nullptr, stream));
-    stage_call_begin(stream);
-    if (decode_path(*shape, tokens)) {
-        // One kernel routes, runs the experts and (in one of its workgroups, at the end) evaluates the
-        // prediction gate.
-        const DecodeRoute r = {w_gate, gate_bias, topk_idx, topk_w, counts, accumulate, w_gate_next, gate_bias_next, pred_idx};
-        return dev(launch_decode_layer(*shape, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags, stream));
+    uint32_t* word = static_cast<uint32_t*>(workspace) + kDecodeStatusWord;  // the flag block starts the workspace
+    uint32_t value = 0;
+    if (hipMemcpyAsync(&value, word, sizeof(value), hipMemcpyDeviceToHost, stream) != hipSuccess) return MOE_ERR_DEVICE;
+    if (hipStreamSynchronize(stream) != hipSuccess) return MOE_ERR_DEVICE;
+    *gave_up = value == kDecodeGaveUp ? 1 : 0;
+    if (reset != 0) {
+        const uint32_t zero = 0;
+        if (hipMemcpyAsync(word, &zero, sizeof(zero), hipMemcpyHostToDevice, stream) != hipSuccess) return MOE_ERR_DEVICE;
+        if (hipStreamSynchronize(stream) != hipSuccess) return MOE_ERR_DEVICE;
     }
-    GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
-    const int n_gates = w_gate_next != nullptr ? 2 : 1;
-    hipError_t e = run_route(*shape, tokens, x, g, n_gates, counts, accumulate, nullptr, !stream_path(*shape, tokens), ws,
-                             stream);
-    if (e != hipSuccess) return MOE_ERR_DEVICE;
-    return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+    return MOE_OK;
+}
+
+int moe_measure_set_decode_spin_limit(int32_t polling_rounds) {
+    if (polling_rounds < 0) return MOE_ERR_SHAPE;
+    g_decode_spin_limit = polling_rounds;
+    return MOE_OK;
 }
 
 int moe_stage_timing_begin(int32_t max_calls) {

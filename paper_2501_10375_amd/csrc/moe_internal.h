@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "moe.h"
+#include "moe_measure.h"
 
 namespace moe {
 
@@ -26,14 +27,17 @@ constexpr int kStreamMaxTokens = 32;
 constexpr int kTileTokensF32 = 64;
 constexpr int kTileTokensBf16 = 256;
 
+// The two blocks of flags and counters come first, at offsets that depend on nothing: calls of any
+// size on one workspace then never put other data where a decode-size call keeps its launch count
+// and arrival flags.
 struct WorkspaceLayout {
+    size_t dec_flags;    // uint32 [kDecodeFlagInts]  arrival flags, launch count and status word of the decode kernel's two grid-wide rendezvous
+    size_t sync;         // int32 [kSyncInts]    rendezvous / arrival counters of the two grouped GEMMs
     size_t hist;         // int32 [n_blocks, E]  per-block selection histogram
     size_t hist_next;    // int32 [n_blocks, E]  same for the next-layer gate
     size_t offs;         // int32 [E + 1]        exclusive scan of counts
     size_t row_of_slot;  // int32 [A]            slot -> assignment index t*k + j
     size_t slot_of;      // int32 [A]            assignment index -> slot
-    size_t sync;         // int32 [kSyncInts]    rendezvous / arrival counters of the two grouped GEMMs
-    size_t dec_flags;    // uint32 [kDecodeFlagInts]  arrival flags and launch count of the decode kernel's two grid-wide rendezvous
     size_t route_end;    // bytes needed by routing-only calls
     size_t act;          // dtype [A, F]         silu(W1 x) * (W3 x)
     size_t out;          // fp32  [A, H]         per-assignment expert output
@@ -56,12 +60,12 @@ struct GateArgs {
     int32_t* hist;     // [n_blocks, E] or null
 };
 
-// Stage ids of the optional per-stage timing (moe_stage_timing_begin/end in moe.h).
+// Stage ids of the optional per-stage timing (moe_stage_timing_begin/end in moe_measure.h).
 enum Stage {
     kStageRoute = 0, kStagePermute = 1, kStageGemm1 = 2, kStageGemm2 = 3, kStageCombine = 4,
     kStageFused = 5,  // the single kernel of a decode-size bf16 call
 };
-static_assert(kStageFused + 1 == MOE_NUM_STAGES, "moe.h lists the stages");
+static_assert(kStageFused + 1 == MOE_NUM_STAGES, "moe_measure.h lists the stages");
 // Records "stage `stage` ends here" on `stream`; a no-op unless timing is active on this thread.
 void stage_mark(hipStream_t stream, int stage);
 
@@ -117,6 +121,12 @@ int compute_units();
 // whose contents need not be initialised (two arrays of 256 arrival flags, one per workgroup and
 // rendezvous, and the launch count the flags' epoch is derived from; the grid is at most 256 workgroups).
 constexpr int kDecodeFlagInts = 2 * 256 + 16;
+// Word of that block that a rendezvous which gave up sets to kDecodeGaveUp (read by moe_decode_status).
+constexpr int kDecodeStatusWord = 2 * 256 + 1;
+constexpr uint32_t kDecodeGaveUp = 0xDEC0DEADu;
+// Polling rounds a rendezvous of the decode kernel waits before it gives up (2^22 unless a test
+// lowered it through moe_measure_set_decode_spin_limit).
+int decode_spin_limit();
 struct DecodeRoute {
     const void* w_gate;
     const float* bias;

@@ -23,8 +23,10 @@ STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTY
           -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE"}
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
-           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_stage_timing_begin", "moe_stage_timing_end",
-           "moe_calibrate_mfma", "moe_calibrate_read_stream")
+           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_decode_status",
+           # include/moe_measure.h
+           "moe_stage_timing_begin", "moe_stage_timing_end", "moe_calibrate_mfma", "moe_calibrate_read_stream",
+           "moe_measure_set_decode_spin_limit")
 STAGES = ("route", "permute", "gemm1", "gemm2", "combine", "fused")
 
 
@@ -65,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn.restype = ctypes.c_int
         L.moe_layer.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.moe_layer.restype = ctypes.c_int
+        L.moe_decode_status.argtypes = [vp, sz, i32, ctypes.POINTER(i32), vp]
+        L.moe_decode_status.restype = ctypes.c_int
+        L.moe_measure_set_decode_spin_limit.argtypes = [i32]
+        L.moe_measure_set_decode_spin_limit.restype = ctypes.c_int
         L.moe_stage_timing_begin.argtypes = [i32]
         L.moe_stage_timing_begin.restype = ctypes.c_int
         L.moe_stage_timing_end.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -178,6 +184,18 @@ def moe_layer(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next
                            _p(counts, torch.int32, (E,), "counts"), int(bool(accumulate)),
                            _p(pred_idx, torch.int32, (T, k), "pred_idx"),
                            _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()), "moe_layer")
+
+
+def moe_decode_status(workspace: torch.Tensor, reset: bool = False) -> bool:
+    """True if a decode-size call on this workspace gave up a rendezvous since the last reset (synchronises)."""
+    out = ctypes.c_int32(0)
+    _check(lib().moe_decode_status(_p(workspace, torch.uint8, None, "workspace"), workspace.numel(), int(bool(reset)),
+                                   ctypes.byref(out), _stream()), "moe_decode_status")
+    return bool(out.value)
+
+
+def moe_measure_set_decode_spin_limit(polling_rounds: int):
+    _check(lib().moe_measure_set_decode_spin_limit(int(polling_rounds)), "moe_measure_set_decode_spin_limit")
 
 
 class PreparedLayerCall:

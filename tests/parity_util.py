@@ -84,3 +84,40 @@ def check_layer(oracle, d_gpu, shape, out, dtype, tokens=None, label="", predict
     assert np.all(np.isfinite(y_gpu))
     assert err <= TOL[dtype], f"{label}: output error {err:.3e} > {TOL[dtype]:.0e}"
     return {"excluded": n_excl, "excluded_pred": n_excl_pred, "err": err, "compared_tokens": int(tok.size)}
+
+
+def tile_aware_sample(idx: np.ndarray, n_experts: int, n_even: int, tile: int = 256, n_cold: int = 2,
+                      fragment: int = 32) -> np.ndarray:
+    """Tokens on which to compare the layer output of a long call, chosen from where the grouped GEMMs
+    put them.  Selections are grouped per expert in (token, j) order (a stable sort), `tile` slots to
+    a slot tile.  The sample holds
+      * every token routed to one of the `n_cold` least-used experts (their few, ragged slot tiles are
+        the ones whose K range is split between workgroups when they fall into the last round),
+      * the first and last slot of every slot tile of every expert,
+      * for the most-used expert's first and last slot tile, one slot at the start and one at the end of
+        every `fragment`-slot group (every fragment position of a tile, full and ragged),
+      * `n_even` evenly spaced tokens.
+    idx: int [T, k] selected experts."""
+    T, k = idx.shape
+    flat = idx.ravel()
+    order = np.argsort(flat, kind="stable")          # slot -> assignment t*k+j
+    counts = np.bincount(flat, minlength=n_experts)
+    starts = np.concatenate([[0], np.cumsum(counts)])
+    chosen = set(np.unique(np.linspace(0, T - 1, max(n_even, 1)).astype(int)).tolist())
+    used = [e for e in np.argsort(counts, kind="stable") if counts[e] > 0]
+    for e in used[:n_cold]:
+        chosen.update((order[starts[e]:starts[e + 1]] // k).tolist())
+    for e in used:
+        c = int(counts[e])
+        for s0 in range(0, c, tile):
+            last = min(c, s0 + tile) - 1
+            chosen.add(int(order[starts[e] + s0] // k))
+            chosen.add(int(order[starts[e] + last] // k))
+    if used:
+        e = used[-1]
+        c = int(counts[e])
+        for s0 in {0, (c - 1) // tile * tile}:
+            for f0 in range(s0, min(c, s0 + tile), fragment):
+                chosen.add(int(order[starts[e] + f0] // k))
+                chosen.add(int(order[starts[e] + min(c, f0 + fragment) - 1] // k))
+    return np.array(sorted(chosen), dtype=np.int64)

@@ -8,6 +8,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "moe.h")
+MEASURE_HEADER = os.path.join(ROOT, "include", "moe_measure.h")
 POLICY_HEADER = os.path.join(ROOT, "include", "daop_policy.h")
 
 
@@ -35,9 +36,12 @@ def test_header_declares_the_four_entry_points():
 def test_library_exports_every_declared_symbol(L):
     from paper_2501_10375_amd import moe
 
-    for name in _declared_functions():
+    layer, measure = _declared_functions(), _declared_functions(MEASURE_HEADER)
+    for name in layer + measure:
         assert hasattr(L, name), name
-    assert set(moe.EXPORTS) == set(_declared_functions())
+    assert set(moe.EXPORTS) == set(layer) | set(measure)
+    # the layer's header declares nothing that allocates, keeps state or times itself
+    assert not [n for n in layer if n.startswith(("moe_stage_", "moe_calibrate_", "moe_measure_"))]
     from paper_2501_10375_amd import policy
 
     declared = _declared_functions(POLICY_HEADER, "daop_")
@@ -207,3 +211,30 @@ def test_read_stream_call_validates_on_the_host(L):
     assert L.moe_calibrate_read_stream(None, 1 << 30, ctypes.byref(ms), ctypes.byref(nbytes), None) == -1      # NULL buffer
     assert L.moe_calibrate_read_stream(ctypes.c_void_p(4096), 1 << 30, None, ctypes.byref(nbytes), None) == -1  # NULL output
     assert L.moe_calibrate_read_stream(ctypes.c_void_p(4100), 1 << 30, ctypes.byref(ms), ctypes.byref(nbytes), None) == -5  # alignment
+
+
+def test_decode_status_call_validates_on_the_host(L):
+    from paper_2501_10375_amd import moe
+
+    out = ctypes.c_int32(7)
+    fake = ctypes.c_void_p(0x1000)
+    assert L.moe_decode_status(None, 1 << 20, 0, ctypes.byref(out), None) == moe.MOE_ERR_NULL
+    assert L.moe_decode_status(fake, 1 << 20, 0, None, None) == moe.MOE_ERR_NULL
+    assert L.moe_decode_status(ctypes.c_void_p(0x1004), 1 << 20, 0, ctypes.byref(out), None) == moe.MOE_ERR_ALIGN
+    assert L.moe_decode_status(fake, 64, 0, ctypes.byref(out), None) == moe.MOE_ERR_WORKSPACE
+    assert out.value == 7
+    assert L.moe_measure_set_decode_spin_limit(-1) == moe.MOE_ERR_SHAPE
+
+
+def test_workspace_keeps_flags_and_counters_at_fixed_offsets(L):
+    """The decode kernel's launch count and arrival flags and the GEMMs' counters sit at the start of
+    the workspace whatever the call size, so a long call can never put other data over them: the
+    smallest workspace (0 tokens) already holds both blocks, and every size's routing part starts
+    with them."""
+    n0, n = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    s = _shape()
+    assert L.moe_route_workspace_bytes(ctypes.byref(s), 0, ctypes.byref(n0)) == 0
+    assert n0.value >= (2 * 256 + 16) * 4 + 2 * (8 + 8 * 32) * 4
+    for T in (1, 16, 17, 1024, 4096):
+        assert L.moe_route_workspace_bytes(ctypes.byref(s), T, ctypes.byref(n)) == 0
+        assert n.value >= n0.value

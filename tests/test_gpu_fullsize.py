@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2501_10375_amd import moe, synth
-from parity_util import check_layer
+from parity_util import check_layer, tile_aware_sample
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -33,14 +33,19 @@ def phi():
     torch.cuda.empty_cache()
 
 
-def _layer(oracle, d, c, T, n_sample, label):
+def _layer(oracle, d, c, T, n_sample, label, tile_aware=False):
     shape = moe.make_shape(c["H"], c["F"], c["E"], c["k"], torch.bfloat16)
     call = dict(d, x=d["x"][:T].contiguous())
     out = moe.LayerOutputs(shape, T, torch.bfloat16, DEV)
     res = moe.run_layer(shape, call, out)
     torch.cuda.synchronize()
     assert int(res["counts"].sum().item()) == T * c["k"]
-    tokens = None if n_sample >= T else np.unique(np.linspace(0, T - 1, n_sample).astype(int))
+    if n_sample >= T:
+        tokens = None
+    elif tile_aware:
+        tokens = tile_aware_sample(res["idx"].cpu().numpy(), c["E"], n_sample)
+    else:
+        tokens = np.unique(np.linspace(0, T - 1, n_sample).astype(int))
     r = check_layer(oracle, call, shape, res, torch.bfloat16, tokens=tokens, label=label)
     print(label, r, "counts", res["counts"].tolist(), flush=True)
     assert r["excluded"] <= max(2, 0.01 * T)
@@ -57,15 +62,20 @@ def test_mixtral_mid_sizes(oracle, mixtral, T):
     _layer(oracle, mixtral, MIXTRAL, T, 32, f"mixtral T={T}")
 
 
-@pytest.mark.parametrize("T", [512, 4096])
+@pytest.mark.parametrize("T", [512, 2048, 4096])
 def test_mixtral_prefill(oracle, mixtral, T):
-    r, res = _layer(oracle, mixtral, MIXTRAL, T, 24, f"mixtral prefill T={T}")
+    """The three prefill lengths of the benchmark.  The output is compared on every token of the two
+    least-used experts, both ends of every slot tile, every fragment position of the busiest expert's
+    first and last tile, and an even sample: several hundred tokens per length."""
+    r, res = _layer(oracle, mixtral, MIXTRAL, T, 256, f"mixtral prefill T={T}", tile_aware=True)
+    assert r["compared_tokens"] >= 250
     share = res["counts"].float() / res["counts"].sum()
     assert share[0] > 0.3 and share[-1] < 0.06  # the Zipf(1.2) skew of the benchmark recipe
 
 
 def test_phi_prefill_and_decode(oracle, phi):
-    r, res = _layer(oracle, phi, PHI, 2048, 24, "phi prefill T=2048")
+    r, res = _layer(oracle, phi, PHI, 2048, 256, "phi prefill T=2048", tile_aware=True)
+    assert r["compared_tokens"] >= 250
     top4 = torch.sort(res["counts"], descending=True).values[:4].sum().item() / res["counts"].sum().item()
     assert top4 > 0.8  # four experts take most tokens (load-imbalance stress)
     _layer(oracle, phi, PHI, 1, 1, "phi decode T=1")

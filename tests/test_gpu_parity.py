@@ -46,6 +46,25 @@ def test_bf16_prefill_path(oracle, T, H, F, E, k):
 
 
 @pytest.mark.parametrize("T,H,F,E,k", [
+    (1100, 256, 512, 2, 2),    # ~9 slot tiles of 256, everything in one split round (gemm1 2 K parts, gemm2 4)
+    (700, 512, 384, 1, 1),     # one expert, top-1: a dense SwiGLU MLP; F = 3 feature tiles of gemm1
+    (1300, 320, 448, 2, 2),    # F ends in a half feature tile, K = 5 steps of 64 (odd number of ring turns)
+    (2100, 1024, 320, 4, 2),   # 16 K steps: the two-stage ring wraps 8 times; ragged last slot tiles
+    (3000, 256, 2048, 2, 2),   # more tiles than compute units: one full round, then a split round
+])
+def test_bf16_full_tile_flavour_every_token(oracle, T, H, F, E, k):
+    """Calls with at least 512 routed rows per expert take the branch-free GEMM flavour (256-slot
+    tiles, two LDS stages, no fragment skipping), the one long prefill calls run.  Narrow layers let
+    the oracle check every token, so every wavefront's fragment rows and every epilogue position of
+    the 256 x 256 tile is compared, including tiles whose K range is split between workgroups."""
+    assert T * k >= E * 512
+    d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
+    r = check_layer(oracle, d, shape, res, torch.bfloat16, label=f"bf16 full tiles T={T}")
+    print(r)
+    assert r["compared_tokens"] >= T - r["excluded"] - 2
+
+
+@pytest.mark.parametrize("T,H,F,E,k", [
     (1, 256, 512, 8, 2), (5, 256, 512, 8, 2), (16, 256, 512, 8, 2), (8, 512, 1600, 16, 2), (3, 64, 64, 4, 1),
     (16, 128, 320, 8, 8), (7, 2048, 1024, 8, 2), (4, 128, 128, 64, 8), (9, 192, 256, 32, 2), (6, 8192, 128, 8, 2),
     (5, 128, 128, 6, 2),
@@ -145,6 +164,59 @@ def test_sequence_of_calls_on_one_workspace_small_shapes(T, H, F, E, k):
         torch.cuda.synchronize()
         assert torch.equal(idx, ref["idx"]) and torch.equal(pred, ref["pred_idx"]), f"step {step}"
         assert torch.equal(y.view(torch.int16), ref["y"].view(torch.int16)), f"step {step}"
+
+
+def test_alternating_long_and_decode_calls_on_one_workspace():
+    """A serving loop alternates prefill-size and single-token calls on one workspace.  The decode
+    kernel derives its rendezvous epoch from a launch count it keeps in the workspace, and flags left
+    by its previous launch carry the previous epoch; a long call in between must leave both alone
+    (they sit at fixed offsets ahead of everything whose size depends on the call).  Every call is
+    compared bit for bit with the same call on a fresh workspace filled with a byte pattern."""
+    H, F, E, k, dtype = 256, 512, 8, 2, torch.bfloat16
+    d = synth.moe_layer_inputs(1024, H, F, E, dtype, DEV, seed=11, zipf_s=1.2, with_next=True)
+    shape = moe.make_shape(H, F, E, k, dtype)
+    shared = moe.LayerOutputs(shape, 1024, dtype, DEV, predict=True)
+    shared.workspace.zero_()
+    for step, T in enumerate([1, 1024, 1, 1, 1024, 300, 1, 24, 1, 1024, 1]):
+        call = dict(d, x=synth.normal((T, H), 4000 + step, synth.TID_X, 1.0, dtype, DEV))
+        got = moe.run_layer(shape, call, shared, predict=True)
+        y, idx = got["y"].clone(), got["idx"].clone()
+        fresh = moe.LayerOutputs(shape, T, dtype, DEV, predict=True)
+        fresh.workspace.fill_(0x5A)
+        ref = moe.run_layer(shape, call, fresh, predict=True)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, ref["idx"]), f"step {step} T={T}"
+        assert torch.equal(y.view(torch.int16), ref["y"].view(torch.int16)), f"step {step} T={T}"
+    assert not moe.moe_decode_status(shared.workspace)
+
+
+def test_decode_rendezvous_reports_when_it_gives_up(oracle):
+    """The decode-size kernel's workgroups wait for one another with a bounded spin.  Normally nobody
+    gives up and the status word stays clear.  With the spin bound lowered to zero from the host every
+    rendezvous gives up at once (all kernels still run to their end): the call then reports it through
+    moe_decode_status and marks its output with NaN instead of returning numbers computed from an
+    intermediate that may not have been written yet."""
+    T, H, F, E, k, dtype = 4, 256, 512, 8, 2, torch.bfloat16
+    d, shape, out, res = _run(T, H, F, E, k, dtype)
+    torch.cuda.synchronize()
+    good = res["y"].clone()
+    assert not moe.moe_decode_status(out.workspace, reset=True)
+    try:
+        moe.moe_measure_set_decode_spin_limit(0)
+        res = moe.run_layer(shape, d, out)
+        torch.cuda.synchronize()
+        assert torch.isnan(res["y"].float()).all()
+        assert moe.moe_decode_status(out.workspace)            # reported ...
+        assert moe.moe_decode_status(out.workspace, reset=True)  # ... and sticky until reset
+        assert not moe.moe_decode_status(out.workspace)
+    finally:
+        moe.moe_measure_set_decode_spin_limit(1 << 22)
+    res = moe.run_layer(shape, d, out)
+    torch.cuda.synchronize()
+    assert torch.equal(res["y"].view(torch.int16), good.view(torch.int16))
+    assert not moe.moe_decode_status(out.workspace)
+    r = check_layer(oracle, d, shape, res, dtype, label="after a reported give-up")
+    print(r)
 
 
 def test_prepared_call_equals_run_layer():

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2501_10375_amd import moe, policy, stack, synth
-from parity_util import check_layer, host
+from parity_util import check_layer, check_routing, host, tile_aware_sample
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -72,6 +72,60 @@ def test_small_stack_teacher_forced_parity(oracle):
     covered_before = (P * before.int()).sum().item()
     covered_after = (P * cache.int()).sum().item()
     assert covered_after >= covered_before   # more prefill tokens hit GPU-resident experts after the swaps
+
+
+@pytest.mark.timeout(900)
+def test_full_size_stack_teacher_forced_parity(oracle):
+    """The benchmark's multi-layer workload at its real size: 32 resident Mixtral-shaped layers
+    (Table III; 90 GB of expert weights), a 1024-token prefill and one single-token decode step.
+    Teacher-forced: each layer's oracle sees the input the GPU's layer saw.  Routing, counts and the
+    prediction are compared on every token of every layer; layer outputs on layers 0, 1, 4, 15 and 31
+    (sampled prefill tokens chosen by slot-tile position, and the decode token)."""
+    L, H, F, E, k, T = 32, 4096, 14336, 8, 2, 1024
+    free, _ = torch.cuda.mem_get_info()
+    need = L * E * 3 * H * F * 2 + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free device memory, {free >> 30} GiB available")
+    st = stack.MoeStack(L, H, F, E, k, torch.bfloat16, DEV, zipf_s=1.2, max_tokens=T)
+    assert abs(st.weight_bytes() / 1e9 - 90.2) < 0.1
+    sampled_layers = (0, 1, 4, 15, 31)
+    for phase, tokens, seed in (("prefill", T, 999), ("decode", 1, 1000)):
+        h0 = synth.normal((tokens, H), seed, synth.TID_X, 1.0, torch.float32, DEV)
+        counts = st.new_counts()
+        out = st.forward(h0, counts, keep_inputs=True, keep_outputs=True)
+        torch.cuda.synchronize()
+        assert counts[:, :E].sum(1).tolist() == [tokens * k] * L
+        idx, pred = out["idx"].clone(), out["pred"].clone()
+        excluded = 0
+        for l in range(L):
+            nxt = st.layers[l + 1] if l + 1 < L else None
+            y, w = out["outputs"][l]
+            label = f"full stack {phase} layer {l}"
+            print(label, flush=True)
+            if l in sampled_layers:
+                d = dict(st.layers[l], x=out["inputs"][l])
+                d["wg_next"], d["bias_next"] = (nxt["wg"], nxt["bias"]) if nxt else (None, None)
+                res = {"y": y, "idx": idx[l], "w": w, "counts": counts[l, :E], "pred_idx": pred[l] if nxt else None}
+                sample = None if tokens <= 64 else tile_aware_sample(idx[l].cpu().numpy(), E, 32, n_cold=1)
+                r = check_layer(oracle, d, st.shape, res, torch.bfloat16, tokens=sample, label=label,
+                                predict=nxt is not None)
+                print(label, r, flush=True)
+                assert r["compared_tokens"] >= min(tokens, 32)
+                excluded += r["excluded"] + r["excluded_pred"]
+            else:
+                x = synth.to_numpy(out["inputs"][l])
+                d = st.layers[l]
+                ref = oracle.route(x, synth.to_numpy(d["wg"]), synth.to_numpy(d["bias"]), k)
+                n, _ = check_routing(idx[l], w, counts[l, :E], ref, E, label)
+                excluded += n
+                if nxt is not None:
+                    pref = oracle.predict_next(x, synth.to_numpy(nxt["wg"]), synth.to_numpy(nxt["bias"]), k)
+                    n, _ = check_routing(pred[l], None, None, pref, E, label + " (prediction)")
+                    excluded += n
+        assert excluded <= 0.01 * 2 * L * tokens + 2
+        del out
+    del st
+    torch.cuda.empty_cache()
 
 
 def test_precalculation_variant(oracle):
