@@ -71,7 +71,8 @@ typedef enum {
     MOE_ERR_DTYPE = -3,     /* dtype is not a moe_dtype_t value                   */
     MOE_ERR_WORKSPACE = -4, /* workspace_bytes is smaller than the call needs     */
     MOE_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned                   */
-    MOE_ERR_DEVICE = -6     /* a kernel launch failed (hipGetLastError != success) */
+    MOE_ERR_DEVICE = -6,    /* a kernel launch failed (hipGetLastError != success) */
+    MOE_ERR_TOO_LARGE = -7  /* moe_layer_static: the call needs more than MOE_STATIC_SCRATCH_BYTES */
 } moe_status_t;
 
 typedef enum {
@@ -164,6 +165,32 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
               size_t workspace_bytes, void* hip_stream);
 
 /*
+ * moe_layer for callers that cannot provide or allocate a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid device
+ * allocation.  Same arguments, kernels and results as moe_layer (bit for bit),
+ * but the scratch memory is a static device array of MOE_STATIC_SCRATCH_BYTES
+ * inside the library (each GPU the library runs on holds one until the process
+ * ends), so the call allocates nothing, neither on the host nor on the device.
+ * A call whose moe_workspace_bytes(shape, tokens) exceeds that size returns
+ * MOE_ERR_TOO_LARGE and enqueues nothing: the buffer is sized for decode steps
+ * (every bf16 call of at most 32 tokens at the shapes of Table III fits, and
+ * fp32 calls of a few hundred tokens at small widths; bf16 calls of more than
+ * 32 tokens never fit, their K-split pieces alone take 64 MiB).
+ * All calls on one GPU share that GPU's array, whatever the stream or thread:
+ * two moe_layer_static calls that overlap in time on one GPU race.  Order them
+ * on one stream or with events.  Nothing in the array needs clearing between
+ * calls (the kernels reset what they need, as with a caller's workspace).
+ * The first call on a device looks up the array's device address (no
+ * allocation); do that once before a stream capture begins.
+ * moe_decode_status(NULL, 0, ...) reads the status word of this array.
+ */
+#define MOE_STATIC_SCRATCH_BYTES (16u << 20)
+int moe_layer_static(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate,
+                     const float* gate_bias, const void* w_gate_next, const float* gate_bias_next,
+                     const void* w1, const void* w3, const void* w2, void* y, int32_t* topk_idx,
+                     float* topk_w, int32_t* counts, int32_t accumulate, int32_t* pred_idx, void* hip_stream);
+
+/*
  * Whether a decode-size call on `workspace` gave up a rendezvous (see the
  * conventions above: bf16 calls of at most 32 tokens need the whole grid
  * resident at once; a workgroup whose bounded wait runs out stores NaN instead
@@ -174,6 +201,8 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
  * cannot be recorded into a graph.  A workspace that was never used by a
  * decode-size call holds arbitrary bytes there; they read as "gave up" only
  * if they equal a 32-bit magic value.
+ * workspace == NULL (workspace_bytes ignored) means the static scratch of
+ * moe_layer_static on the current device.
  * Errors: MOE_ERR_NULL, MOE_ERR_ALIGN, MOE_ERR_WORKSPACE (fewer than 4096
  * bytes), MOE_ERR_DEVICE.
  */

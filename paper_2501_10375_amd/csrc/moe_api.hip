@@ -3,6 +3,15 @@
 #include "moe_internal.h"
 #include "moe_measure.h"
 
+// Scratch of moe_layer_static: what the other entry points take as `workspace`, in a static device
+// array.  Every device the library runs on holds its own copy at its own address; in host code the
+// name below is only a handle for hipGetSymbolAddress, which static_scratch() calls once per device
+// and whose result is what kernels, copies and carve() get.  (No __attribute__((used)) here: with it
+// the compiler keeps the device-side variable at internal linkage, the code object then exports no
+// such symbol and the runtime aborts in the lookup.  The reference from host code below is what makes
+// the compiler export it.)
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
+
 namespace moe {
 
 static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -67,6 +76,21 @@ void stage_mark(hipStream_t stream, int stage) {
 
 namespace {
 int g_decode_spin_limit = 1 << 22;
+
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device, looked up once per device.
+void* static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (g_static_scratch[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_static_scratch[dev] = ptr;   // a race between threads stores the same address twice
+    }
+    return g_static_scratch[dev];
+}
 }
 int decode_spin_limit() { return g_decode_spin_limit; }
 
@@ -242,6 +266,7 @@ const char* moe_status_string(int status) {
         case MOE_ERR_WORKSPACE: return "workspace too small";
         case MOE_ERR_ALIGN: return "a pointer is not 16-byte aligned";
         case MOE_ERR_DEVICE: return "kernel launch failed";
+        case MOE_ERR_TOO_LARGE: return "the call needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -348,8 +373,28 @@ int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const voi
                          counts, accumulate, pred_idx, carve(workspace, L), static_cast<hipStream_t>(hip_stream));
 }
 
+int moe_layer_static(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate,
+                     const float* gate_bias, const void* w_gate_next, const float* gate_bias_next, const void* w1,
+                     const void* w3, const void* w2, void* y, int32_t* topk_idx, float* topk_w, int32_t* counts,
+                     int32_t accumulate, int32_t* pred_idx, void* hip_stream) {
+    if (int rc = check_layer_args(shape, tokens, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx,
+                                  topk_w, counts, pred_idx))
+        return rc;
+    const WorkspaceLayout L = workspace_layout(*shape, tokens);
+    if (L.total > (size_t)MOE_STATIC_SCRATCH_BYTES) return MOE_ERR_TOO_LARGE;
+    void* ws = static_scratch();
+    if (ws == nullptr) return MOE_ERR_DEVICE;
+    return enqueue_layer(*shape, tokens, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx, topk_w,
+                         counts, accumulate, pred_idx, carve(ws, L), static_cast<hipStream_t>(hip_stream));
+}
+
 int moe_decode_status(void* workspace, size_t workspace_bytes, int32_t reset, int32_t* gave_up, void* hip_stream) {
-    if (workspace == nullptr || gave_up == nullptr) return MOE_ERR_NULL;
+    if (gave_up == nullptr) return MOE_ERR_NULL;
+    if (workspace == nullptr) {  // the static scratch of moe_layer_static on the current device
+        workspace = static_scratch();
+        workspace_bytes = MOE_STATIC_SCRATCH_BYTES;
+        if (workspace == nullptr) return MOE_ERR_DEVICE;
+    }
     if (misaligned(workspace)) return MOE_ERR_ALIGN;
     if (workspace_bytes < kDecodeFlagInts * sizeof(uint32_t)) return MOE_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);

@@ -19,11 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK, MOE_ERR_NULL, MOE_ERR_SHAPE, MOE_ERR_DTYPE, MOE_ERR_WORKSPACE, MOE_ERR_ALIGN, MOE_ERR_DEVICE = 0, -1, -2, -3, -4, -5, -6
+MOE_ERR_TOO_LARGE = -7
+MOE_STATIC_SCRATCH_BYTES = 16 << 20
 STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTYPE", -4: "MOE_ERR_WORKSPACE",
-          -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE"}
+          -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE", -7: "MOE_ERR_TOO_LARGE"}
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
-           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_decode_status",
+           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_layer_static", "moe_decode_status",
            # include/moe_measure.h
            "moe_stage_timing_begin", "moe_stage_timing_end", "moe_calibrate_mfma", "moe_calibrate_read_stream",
            "moe_measure_set_decode_spin_limit")
@@ -67,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn.restype = ctypes.c_int
         L.moe_layer.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.moe_layer.restype = ctypes.c_int
+        L.moe_layer_static.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+        L.moe_layer_static.restype = ctypes.c_int
         L.moe_decode_status.argtypes = [vp, sz, i32, ctypes.POINTER(i32), vp]
         L.moe_decode_status.restype = ctypes.c_int
         L.moe_measure_set_decode_spin_limit.argtypes = [i32]
@@ -186,10 +190,28 @@ def moe_layer(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next
                            _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()), "moe_layer")
 
 
-def moe_decode_status(workspace: torch.Tensor, reset: bool = False) -> bool:
-    """True if a decode-size call on this workspace gave up a rendezvous since the last reset (synchronises)."""
+def moe_layer_static(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx, topk_w,
+                     counts, accumulate: bool, pred_idx):
+    """moe_layer on the library's static scratch buffer (no workspace argument, nothing allocated)."""
+    T, E, k, H, F = x.shape[0], shape.n_experts, shape.top_k, shape.hidden, shape.ffn
+    dt = x.dtype
+    _check(lib().moe_layer_static(ctypes.byref(shape), T, _p(x, None, (T, H), "x"), _p(w_gate, dt, (E, H), "w_gate"),
+                                  _p(gate_bias, torch.float32, (E,), "gate_bias"),
+                                  _p(w_gate_next, dt, (E, H), "w_gate_next"),
+                                  _p(gate_bias_next, torch.float32, (E,), "gate_bias_next"),
+                                  _p(w1, dt, (E, F, H), "w1"), _p(w3, dt, (E, F, H), "w3"), _p(w2, dt, (E, H, F), "w2"),
+                                  _p(y, dt, (T, H), "y"), _p(topk_idx, torch.int32, (T, k), "topk_idx"),
+                                  _p(topk_w, torch.float32, (T, k), "topk_w"), _p(counts, torch.int32, (E,), "counts"),
+                                  int(bool(accumulate)), _p(pred_idx, torch.int32, (T, k), "pred_idx"), _stream()),
+           "moe_layer_static")
+
+
+def moe_decode_status(workspace: torch.Tensor | None, reset: bool = False) -> bool:
+    """True if a decode-size call on this workspace (None: the static scratch of moe_layer_static) gave
+    up a rendezvous since the last reset (synchronises)."""
     out = ctypes.c_int32(0)
-    _check(lib().moe_decode_status(_p(workspace, torch.uint8, None, "workspace"), workspace.numel(), int(bool(reset)),
+    _check(lib().moe_decode_status(_p(workspace, torch.uint8, None, "workspace"),
+                                   0 if workspace is None else workspace.numel(), int(bool(reset)),
                                    ctypes.byref(out), _stream()), "moe_decode_status")
     return bool(out.value)
 

@@ -72,7 +72,7 @@ def test_policy_calls_reject_bad_arguments_on_the_host(L):
 
 
 def test_status_strings(L):
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         s = L.moe_status_string(code)
         assert s and b"unknown" not in s
     assert b"unknown" in L.moe_status_string(-99)
@@ -218,8 +218,8 @@ def test_decode_status_call_validates_on_the_host(L):
 
     out = ctypes.c_int32(7)
     fake = ctypes.c_void_p(0x1000)
-    assert L.moe_decode_status(None, 1 << 20, 0, ctypes.byref(out), None) == moe.MOE_ERR_NULL
     assert L.moe_decode_status(fake, 1 << 20, 0, None, None) == moe.MOE_ERR_NULL
+    assert L.moe_decode_status(None, 0, 0, None, None) == moe.MOE_ERR_NULL
     assert L.moe_decode_status(ctypes.c_void_p(0x1004), 1 << 20, 0, ctypes.byref(out), None) == moe.MOE_ERR_ALIGN
     assert L.moe_decode_status(fake, 64, 0, ctypes.byref(out), None) == moe.MOE_ERR_WORKSPACE
     assert out.value == 7
@@ -238,3 +238,31 @@ def test_workspace_keeps_flags_and_counters_at_fixed_offsets(L):
     for T in (1, 16, 17, 1024, 4096):
         assert L.moe_route_workspace_bytes(ctypes.byref(s), T, ctypes.byref(n)) == 0
         assert n.value >= n0.value
+
+
+def test_static_scratch_entry_point_validates_on_the_host(L):
+    """moe_layer_static checks its arguments and the size limit of its static buffer before any device work."""
+    from paper_2501_10375_amd import moe
+
+    fake = ctypes.c_void_p(0x1000)
+    s = _shape()
+
+    def call(shape, T, x=fake, counts=fake, pred=None, wg_next=None):
+        return L.moe_layer_static(ctypes.byref(shape) if shape is not None else None, T, x, fake, None, wg_next, None,
+                                  fake, fake, fake, fake, fake, fake, counts, 0, pred, None)
+
+    assert call(None, 4) == moe.MOE_ERR_NULL
+    assert call(s, -1) == moe.MOE_ERR_SHAPE
+    assert call(s, 4, x=None) == moe.MOE_ERR_NULL
+    assert call(s, 4, counts=ctypes.c_void_p(0x1008)) == moe.MOE_ERR_ALIGN
+    assert call(s, 4, wg_next=fake) == moe.MOE_ERR_NULL            # prediction asked for, nowhere to put it
+    assert call(_shape(dtype=9), 4) == moe.MOE_ERR_DTYPE
+    # bf16 calls of more than 32 tokens need 64 MiB of K-split pieces: never inside the static buffer
+    assert call(s, 33) == moe.MOE_ERR_TOO_LARGE
+    big = _shape(hidden=4096, ffn=14336, dtype=moe.MOE_F32)
+    assert call(big, 256) == moe.MOE_ERR_TOO_LARGE
+    n = ctypes.c_size_t(0)
+    for shape, T in ((_shape(hidden=4096, ffn=14336), 32), (_shape(hidden=4096, ffn=6400, n_experts=16), 32)):
+        assert L.moe_workspace_bytes(ctypes.byref(shape), T, ctypes.byref(n)) == 0
+        assert n.value <= moe.MOE_STATIC_SCRATCH_BYTES    # decode steps at the shapes of Table III fit
+    assert b"static" in L.moe_status_string(moe.MOE_ERR_TOO_LARGE)
