@@ -29,7 +29,9 @@
  * softmax-over-selected closed form, zero-input and single-expert special
  * cases, E=1 dense SwiGLU and k=E soft mixture against a library matmul,
  * homogeneity, token independence, expert-permutation equivariance, and the
- * count invariants.  No function here is "parity unpinned".
+ * count invariants; the pre-calculation variant against the pinned expert
+ * function (identical inputs, all-fresh, all-stale, and its linearity in the
+ * combine weights).  No function here is "parity unpinned".
  * tests/test_oracle_mutants.py plants mistakes in a copy of this file, one
  * expression at a time, and requires each to fail a pin; it finds the
  * expressions by their text, so it says so when an edit here moves them.
@@ -221,6 +223,68 @@ int oracle_expert_ffn(int T, int H, int F, int E, int k, int dtype, const void *
         }
         free(xt);
         free(a);
+    }
+    return bad ? -1 : 0;
+}
+
+/*
+ * Expert execution with pre-calculated experts (Sec. IV-C "Prediction-based
+ * Expert Pre-Calculation"): an expert of block i+1 that was predicted one block
+ * ahead and does not sit on the GPU has already been started on the hidden
+ * state block i worked on, so its input is that earlier ("stale") state; every
+ * other selected expert sees the block's true input.  Per selection (t, j):
+ *
+ *   in(t, j) = stale[t,j] ? x_stale[t] : x[t]
+ *   y[t]     = sum_j w[t,j] * W2_e ( silu(W1_e in(t,j)) * (W3_e in(t,j)) ),  e = idx[t,j]
+ *
+ * stale: uint8 [T,k], non-zero = the selection was evaluated on x_stale.  The
+ * paper gives no formula; this is its description written out, with the combine
+ * weights supplied by the caller (it does not say whether the predicted or the
+ * actual gate's weights apply).  Other arguments as in oracle_expert_ffn.
+ */
+int oracle_expert_ffn_precalc(int T, int H, int F, int E, int k, int dtype, const void *x,
+                              const void *x_stale, const uint8_t *stale, const int32_t *idx,
+                              const double *w, const void *w1, const void *w3, const void *w2,
+                              const int32_t *tokens, int ns, double *y) {
+    if (T < 0 || H <= 0 || F <= 0 || E <= 0 || k <= 0 || k > E || ns < 0) return -1;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < ns; ++i) {
+        int t = tokens ? tokens[i] : i;
+        if (t < 0 || t >= T) {
+            bad = 1;
+            continue;
+        }
+        double *in = (double *)malloc(sizeof(double) * (size_t)H);
+        double *hid = (double *)malloc(sizeof(double) * (size_t)F);
+        if (!in || !hid) {
+            bad = 1;
+            free(in);
+            free(hid);
+            continue;
+        }
+        double *yt = y + (size_t)i * H;
+        for (int h = 0; h < H; ++h) yt[h] = 0.0;
+        for (int j = 0; j < k; ++j) {
+            size_t sel = (size_t)t * k + j;
+            int e = idx[sel];
+            if (e < 0 || e >= E) {
+                bad = 1;
+                break;
+            }
+            const void *source = stale[sel] ? x_stale : x;
+            for (int h = 0; h < H; ++h) in[h] = load_elem(source, dtype, (size_t)t * H + h);
+            for (int f = 0; f < F; ++f) {
+                size_t wrow = ((size_t)e * F + f) * (size_t)H;
+                double gate = dot_row(w1, dtype, wrow, in, H);
+                double up = dot_row(w3, dtype, wrow, in, H);
+                hid[f] = gate / (1.0 + exp(-gate)) * up;
+            }
+            for (int h = 0; h < H; ++h)
+                yt[h] += w[sel] * dot_row(w2, dtype, ((size_t)e * H + h) * (size_t)F, hid, F);
+        }
+        free(in);
+        free(hid);
     }
     return bad ? -1 : 0;
 }

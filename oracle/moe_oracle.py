@@ -48,6 +48,8 @@ def _load():
         lib.oracle_route.restype = ip
         lib.oracle_expert_ffn.argtypes = [ip, ip, ip, ip, ip, ip, vp, vp, vp, vp, vp, vp, vp, ip, vp]
         lib.oracle_expert_ffn.restype = ip
+        lib.oracle_expert_ffn_precalc.argtypes = [ip, ip, ip, ip, ip, ip, vp, vp, vp, vp, vp, vp, vp, vp, vp, ip, vp]
+        lib.oracle_expert_ffn_precalc.restype = ip
         lib.oracle_num_threads.restype = ip
         lib.oracle_set_num_threads.argtypes = [ip]
         _lib = lib
@@ -137,6 +139,34 @@ def expert_ffn(x, idx, w, w1, w3, w2, tokens=None):
                                    _ptr(w3), _ptr(w2), _ptr(tok), tok.shape[0], _ptr(y))
     if rc != 0:
         raise ValueError("oracle_expert_ffn rejected its arguments")
+    return y
+
+
+def expert_ffn_precalc(x, x_stale, stale, idx, w, w1, w3, w2, tokens=None):
+    """Expert execution where some selections were pre-calculated on an earlier hidden state (Sec. IV-C):
+    selection (t, j) is evaluated on x_stale[t] where stale[t, j] is non-zero, on x[t] otherwise.
+
+    x, x_stale [T,H]; stale [T,k] (bool / uint8); the rest as in ``expert_ffn``.
+    Returns y float64 [len(tokens), H].
+    """
+    x, x_stale, w1, w3, w2 = _c(x), _c(x_stale), _c(w1), _c(w3), _c(w2)
+    T, H = x.shape
+    E, F, H1 = w1.shape
+    if x_stale.shape != (T, H) or H1 != H or w3.shape != (E, F, H) or w2.shape != (E, H, F):
+        raise ValueError("shapes do not match")
+    code = _code(x, x_stale, w1, w3, w2)
+    idx = _c(np.asarray(idx, dtype=np.int32))
+    k = idx.shape[1]
+    w = _c(np.asarray(w, dtype=np.float64))
+    stale = _c((np.asarray(stale) != 0).astype(np.uint8))
+    if idx.shape != (T, k) or w.shape != (T, k) or stale.shape != (T, k):
+        raise ValueError("idx / w / stale must be [T,k]")
+    tok = np.arange(T, dtype=np.int32) if tokens is None else _c(np.asarray(tokens, dtype=np.int32))
+    y = np.empty((tok.shape[0], H), dtype=np.float64)
+    rc = _load().oracle_expert_ffn_precalc(T, H, F, E, k, code, _ptr(x), _ptr(x_stale), _ptr(stale), _ptr(idx), _ptr(w),
+                                           _ptr(w1), _ptr(w3), _ptr(w2), _ptr(tok), tok.shape[0], _ptr(y))
+    if rc != 0:
+        raise ValueError("oracle_expert_ffn_precalc rejected its arguments")
     return y
 
 

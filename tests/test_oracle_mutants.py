@@ -14,6 +14,7 @@ import numpy as np
 import pytest
 
 import test_oracle_ffn as pins_ffn
+import test_oracle_precalc as pins_precalc
 import test_oracle_route as pins_route
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -44,6 +45,15 @@ MUTANTS = [
     ("every selection uses the first expert", "int e = idx[(size_t)t * k + j];", "int e = idx[(size_t)t * k];"),
     ("every selection uses the first weight", "double wj = w[(size_t)t * k + j];", "double wj = w[(size_t)t * k];"),
     ("token list ignored", "int t = tokens ? tokens[i] : i;", "int t = i;"),
+    ("pre-calculation: stale mask inverted", "const void *source = stale[sel] ? x_stale : x;",
+     "const void *source = stale[sel] ? x : x_stale;"),
+    ("pre-calculation: mask of the token's first selection used for all", "const void *source = stale[sel] ? x_stale : x;",
+     "const void *source = stale[(size_t)t * k] ? x_stale : x;"),
+    ("pre-calculation: stale selections dropped", "yt[h] += w[sel] * dot_row(", "yt[h] += (stale[sel] ? 0.0 : w[sel]) * dot_row("),
+    ("pre-calculation: up projection read from w1", "double up = dot_row(w3, dtype, wrow, in, H);",
+     "double up = dot_row(w1, dtype, wrow, in, H);"),
+    ("pre-calculation: silu on the up projection", "hid[f] = gate / (1.0 + exp(-gate)) * up;", "hid[f] = up / (1.0 + exp(-up)) * gate;"),
+    ("pre-calculation: combine weight of the first selection", "yt[h] += w[sel] * dot_row(", "yt[h] += w[(size_t)t * k] * dot_row("),
     ("bf16 widened with the wrong shift", "uint32_t bits = (uint32_t)r[i] << 16;", "uint32_t bits = (uint32_t)r[i] << 15;"),
     ("fp32 rows read with half the stride", "const float *r = (const float *)mat + row_offset;",
      "const float *r = (const float *)mat + row_offset / 2;"),
@@ -63,7 +73,7 @@ def _load_oracle(src_path, lib_path, tag):
 def _pin_calls():
     """Every pin test of the two oracle test files as a zero-argument-but-oracle callable."""
     calls = []
-    for module in (pins_route, pins_ffn):
+    for module in (pins_route, pins_ffn, pins_precalc):
         for name, fn in sorted(vars(module).items()):
             if not name.startswith("test_") or not inspect.isfunction(fn):
                 continue
