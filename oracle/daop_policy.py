@@ -7,6 +7,8 @@ Plain Python / numpy in fp64 and exact integers, written from the paper:
   * plan_swaps        - Algorithm 1 (Sec. IV-B), the expert-cache update of one block.
   * memory_init       - Sec. IV-A, the calibrated initial expert cache.
   * degrade_selection - Sec. IV-C "Graceful Degradation", index substitution given a placement.
+  * window_variation  - Sec. VI-B "Limitation & Future Work": how much a sequence's activation
+                        pattern changes while it is decoded, measured on 15-token windows.
 
 Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this module.  It
 shares no code with the HIP path.
@@ -28,6 +30,11 @@ Readings where the paper is silent (listed in the design notes as well):
     is on the GPU (ties: lower index); with no expert on the GPU the selection is kept.  The
     weights are the selected experts' probabilities renormalised to sum to one; the list stays in
     descending probability.
+  - Windowed variation (Sec. VI-B names the quantity and the window of 15 tokens, nothing more):
+    the decode steps of a sequence are cut into consecutive windows of `window` tokens (a shorter
+    tail is left out); each window gives an L x E matrix of activation counts, exactly like D in
+    Eq. 1; the variation measure is the Eq. 1 similarity of each window with the next one, and
+    their mean over the sequence.  Fewer than two whole windows: no pair, the mean is 0.
 """
 from __future__ import annotations
 
@@ -146,3 +153,27 @@ def degrade_selection(probs, k, on_gpu):
     for e in sel:
         s += probs[e]
     return sel, [probs[e] / s for e in sel]
+
+
+def window_variation(idx, n_experts, window=15):
+    """Sec. VI-B.  idx: int [L, S, k], the experts every layer selected at each of S decode steps of
+    one sequence.  Returns (mean similarity of consecutive windows, per_pair[S // window - 1])."""
+    idx = np.asarray(idx)
+    assert idx.ndim == 3 and window >= 1
+    L, S, k = idx.shape
+    n_windows = S // window
+    patterns = []
+    for v in range(n_windows):
+        counts = np.zeros((L, n_experts), dtype=np.int64)
+        for l in range(L):
+            for step in range(v * window, (v + 1) * window):
+                for j in range(k):
+                    counts[l, int(idx[l, step, j])] += 1
+        patterns.append(counts)
+    per_pair = np.zeros(max(n_windows - 1, 0), dtype=np.float64)
+    for v in range(n_windows - 1):
+        per_pair[v] = similarity(patterns[v], patterns[v + 1])[0]
+    total = 0.0
+    for v in range(per_pair.shape[0]):
+        total += per_pair[v]
+    return (total / per_pair.shape[0] if per_pair.shape[0] > 0 else 0.0), per_pair

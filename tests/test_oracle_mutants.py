@@ -155,6 +155,11 @@ POLICY_MUTANTS = [
     ("degradation drops the best expert", "sel = sel[:-1] + [rest[0]]", "sel = sel[1:] + [rest[0]]"),
     ("degradation whenever any expert is off the GPU", "if not any(on_gpu[e] for e in sel):", "if not all(on_gpu[e] for e in sel):"),
     ("degradation takes the worst on-GPU expert", "sel = sel[:-1] + [rest[0]]", "sel = sel[:-1] + [rest[-1]]"),
+    ("windows overlap by one step", "for step in range(v * window, (v + 1) * window):", "for step in range(v * window, (v + 1) * window + 1):"),
+    ("windows compared with the first one", "similarity(patterns[v], patterns[v + 1])[0]", "similarity(patterns[0], patterns[v + 1])[0]"),
+    ("only the first selection of a step counted", "for j in range(k):\n                    counts[l, int(idx[l, step, j])] += 1", "for j in range(1):\n                    counts[l, int(idx[l, step, j])] += 1"),
+    ("shorter tail kept as a window", "n_windows = S // window", "n_windows = -(-S // window)"),
+    ("variation summed, not averaged", "(total / per_pair.shape[0] if per_pair.shape[0] > 0 else 0.0)", "total"),
     ("degraded weights not renormalised", "return sel, [probs[e] / s for e in sel]", "return sel, [probs[e] for e in sel]"),
 ]
 

@@ -152,3 +152,51 @@ def test_degrade_selection_rules():
             assert idx[0] == 1 and mask[idx[1]] and p[idx[1]] == max(p[e] for e in range(5) if mask[e])
         else:
             assert idx == [1, 2]
+
+
+# ---- Sec. VI-B: variation of the activation pattern over 15-token windows of the decode phase ----
+
+def test_window_variation_hand_worked():
+    # one layer, three experts, top-1, windows of two steps: counts [2,0,0] then [1,1,0] then [0,1,1]
+    idx = np.array([[[0], [0], [1], [0], [2], [1]]])
+    mean, per = pol.window_variation(idx, 3, window=2)
+    assert per.shape == (2,)
+    assert abs(per[0] - 2 / (2 * math.sqrt(2))) < 1e-15      # (2*1) / (|[2,0,0]| |[1,1,0]|)
+    assert abs(per[1] - 1 / 2) < 1e-15                       # (1*1) / (sqrt 2 * sqrt 2)
+    assert abs(mean - (per[0] + per[1]) / 2) < 1e-15
+
+
+def test_window_variation_limits():
+    rng = np.random.default_rng(5)
+    L, E, k, W = 3, 8, 2, 15
+    same = np.tile(np.array([[[1, 4]]]), (L, 4 * W, 1))
+    assert pol.window_variation(same, E)[0] == pytest.approx(1.0, abs=1e-15)      # the pattern never changes
+    a = np.tile(np.array([[[0, 1]]]), (L, W, 1))
+    b = np.tile(np.array([[[2, 3]]]), (L, W, 1))
+    mean, per = pol.window_variation(np.concatenate([a, b, a], axis=1), E)         # disjoint expert sets
+    assert mean == 0.0 and per.tolist() == [0.0, 0.0]
+    # fewer than two whole windows: no pair
+    assert pol.window_variation(same[:, : 2 * W - 1], E) [0] == 0.0 and pol.window_variation(same[:, :W], E)[1].size == 0
+    # a shorter tail is left out; the order of the steps inside a window does not matter
+    idx = np.stack([np.stack([rng.permutation(E)[:k] for _ in range(3 * W + 7)]) for _ in range(L)])
+    full = pol.window_variation(idx, E)
+    assert np.array_equal(pol.window_variation(idx[:, : 3 * W], E)[1], full[1])
+    shuffled = idx.copy()
+    shuffled[:, W:2 * W] = shuffled[:, W:2 * W][:, rng.permutation(W)]
+    assert np.array_equal(pol.window_variation(shuffled, E)[1], full[1])
+    # window = 15 is the default
+    assert np.array_equal(pol.window_variation(idx, E, window=15)[1], full[1])
+
+
+def test_window_variation_is_eq1_between_consecutive_window_counts():
+    rng = np.random.default_rng(6)
+    L, E, k, W, S = 4, 6, 2, 5, 20
+    idx = np.stack([np.stack([rng.permutation(E)[:k] for _ in range(S)]) for _ in range(L)])
+    mean, per = pol.window_variation(idx, E, window=W)
+
+    def counts(v):   # library histogram of one window, per layer
+        return np.stack([np.bincount(idx[l, v * W:(v + 1) * W].ravel(), minlength=E) for l in range(L)])
+
+    want = [pol.similarity(counts(v), counts(v + 1))[0] for v in range(S // W - 1)]
+    assert np.array_equal(per, np.array(want)) and mean == pytest.approx(np.mean(want), abs=1e-15)
+    assert counts(0).sum() == L * W * k
