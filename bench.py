@@ -91,12 +91,14 @@ def run_stack(args):
     hs = [synth.normal((1, H), 1000 + s, synth.TID_X, 1.0, torch.float32, dev) for s in range(steps)]
     decode = st.new_counts()
     d_exact = torch.zeros(L - 1, dtype=torch.float64, device=dev)
+    selections = torch.zeros((L, steps, k), dtype=torch.int32, device=dev)   # experts of every layer at every decode step
 
     def decode_loop():
-        for h in hs:
+        for i, h in enumerate(hs):
             o = st.forward(h, decode)
             e, _ = stack.agreement(o["pred"], o["idx"])
             d_exact.add_(e)
+            selections[:, i] = o["idx"][:, 0]
 
     st.forward(hs[0], st.new_counts())
     _, d_wall, d_gpu_ms = timed(decode_loop, L * steps)
@@ -116,6 +118,7 @@ def run_stack(args):
     graph_matches = bool(torch.equal(graph_counts, decode))
     P, D = prefill[:, :E].contiguous(), decode[:, :E].contiguous()
     sim, per = policy.daop_similarity(P, D)
+    win_mean, win_pairs = policy.daop_window_variation(selections, E, 15)   # Sec. VI-B: 15-token decode windows
     cache = policy.daop_memory_init(D, (L * E * 15) // 32)      # expert cache ratio 46.875 %
     resident_before = (P * cache.int()).sum().item() / P.sum().item()
     _, n_swaps = policy.daop_plan_swaps(P, cache)
@@ -152,6 +155,9 @@ def run_stack(args):
                                  "prefill_exact_set_layers_ge_4": exact[3:].mean().item() if L > 4 else None,
                                  "decode_exact_set_mean": (d_exact / steps).mean().item()},
         "eq1_similarity_prefill_vs_decode": sim.item(),
+        "decode_window_variation": {"window_tokens": 15, "window_pairs": int(win_pairs.numel()),
+                                    "mean_similarity_of_consecutive_windows": win_mean.item(),
+                                    "min_pair": win_pairs.min().item() if win_pairs.numel() else None},
         "algorithm1": {"cache_slots": int(cache.sum().item()), "swaps": int(n_swaps.sum().item()),
                        "prefill_tokens_on_resident_experts_before": resident_before,
                        "prefill_tokens_on_resident_experts_after": resident_after},

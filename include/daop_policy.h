@@ -2,7 +2,7 @@
  * daop_policy.h - C ABI of the count-driven policy steps of DAOP (arXiv 2501.10375) that consume
  * what the MoE layer (moe.h) produces: per-layer expert activation counts and next-layer
  * predictions.  All of it is small integer / index work that runs on the device so the counts
- * never leave HBM; every call enqueues one kernel on `hip_stream` and returns.
+ * never leave HBM; every call enqueues one or two small kernels on `hip_stream` and returns.
  *
  * Conventions are those of moe.h: all pointers are DEVICE pointers (dense, row-major, 16-byte
  * aligned), the caller owns every buffer, return value MOE_OK or a negative moe_status_t,
@@ -32,6 +32,20 @@ extern "C" {
  */
 int daop_similarity(int32_t n_layers, int32_t n_experts, const int32_t* counts_p, const int32_t* counts_d,
                     double* out, void* hip_stream);
+
+/*
+ * Variation of a sequence's activation pattern during decoding (Sec. VI-B "Limitation & Future
+ * Work", which measures it on windows of 15 tokens): the decode steps are cut into consecutive
+ * windows of `window` steps (a shorter tail is left out), every window gives an n_layers x
+ * n_experts matrix of activation counts, and each window is compared with the next one by Eq. 1.
+ *   idx  int32 [n_layers, steps, top_k]  in: the experts every layer selected at every decode step
+ *        (moe_layer's topk_idx of step s, layer l at idx[l, s, :]); every index in [0, n_experts)
+ *   out  fp64 [1 + max(steps / window - 1, 0)]  out: out[0] the mean over the window pairs (0 when
+ *        there are fewer than two whole windows), out[1 + v] the similarity of windows v and v + 1
+ * Arithmetic as in daop_similarity.  Limits: steps <= 1048576, 1 <= window <= 4096, 1 <= top_k <= 8.
+ */
+int daop_window_variation(int32_t n_layers, int32_t n_experts, int32_t steps, int32_t top_k, int32_t window,
+                          const int32_t* idx, double* out, void* hip_stream);
 
 /*
  * Algorithm 1 (Sec. IV-B, sequence-specific expert allocation), the cache update of every block

@@ -154,6 +154,28 @@ int moe_expert_ffn(const moe_shape_t* shape, int32_t tokens, const void* x, cons
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Expert execution with pre-calculated experts (Sec. IV-C "Prediction-based
+ * Expert Pre-Calculation"): an expert that was predicted one block ahead and
+ * is not held on the GPU has been started on the hidden state of the block
+ * before, so that selection's input is the earlier state, while every other
+ * selected expert sees the block's true input.  For every token t
+ *   y[t] = sum_j topk_w[t,j] * W2_e ( silu(W1_e in) * (W3_e in) ),  e = topk_idx[t,j],
+ *   in = x_stale[t] where stale[t,j] != 0, else x[t].
+ * One pass over the experts' weights and one rounding of y, as in
+ * moe_expert_ffn, which this call equals bit for bit when stale is all zero.
+ * The paper does not say which gate's weights combine the outputs; the caller
+ * passes them (the harness uses the predicted gate's).
+ *
+ *   x_stale [tokens, H]  in  the hidden states the pre-calculated experts saw, shape->dtype
+ *   stale   [tokens, k]  in  uint8, non-zero = selection (t, j) was evaluated on x_stale
+ *   the other arguments, the workspace and the errors as in moe_expert_ffn
+ */
+int moe_expert_ffn_precalc(const moe_shape_t* shape, int32_t tokens, const void* x, const void* x_stale,
+                           const uint8_t* stale, const int32_t* topk_idx, const float* topk_w, const void* w1,
+                           const void* w3, const void* w2, void* y, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
  * One whole MoE layer: moe_route, then (if w_gate_next is not NULL)
  * moe_predict_next into pred_idx, then moe_expert_ffn, with x read once for
  * both gates.  pred_idx may be NULL only when w_gate_next is NULL.

@@ -1,6 +1,7 @@
 // Count-driven policy steps of DAOP on the device (see include/daop_policy.h for the contract):
-// Eq. 1 similarity of activation patterns, the cache update of Algorithm 1, the calibrated initial
-// cache of Sec. IV-A and next-layer prediction with graceful degradation (Sec. IV-C).  The data is
+// Eq. 1 similarity of activation patterns, its windowed form over a sequence's decode steps
+// (Sec. VI-B), the cache update of Algorithm 1, the calibrated initial cache of Sec. IV-A and
+// next-layer prediction with graceful degradation (Sec. IV-C).  The data is
 // a few kilobytes of integers; each call is one small kernel so the counts the MoE layer leaves in
 // HBM are consumed where they are.
 #include "daop_policy.h"
@@ -35,6 +36,47 @@ __global__ __launch_bounds__(64) void similarity_kernel(int L, int E, const int3
         for (int l = 0; l < L; ++l) total += out[1 + l];
         out[0] = total / (double)L;
     }
+}
+
+// ---- windowed variation (Sec. VI-B) -------------------------------------------------------------
+// Workgroup v compares decode window v with window v + 1: thread l takes layers l, l + 256, ... and
+// forms the three sums of the cosine directly from the selections (for every expert, how often it
+// occurs in either window), in expert order, in fp64: the counts are small integers, so the sums are
+// exact and only the roots, their product and the quotient round, as in the similarity kernel.
+__global__ __launch_bounds__(256) void window_pairs_kernel(int L, int E, int S, int k, int window,
+                                                           const int32_t* __restrict__ idx, double* __restrict__ out) {
+    __shared__ double cosine[kMaxLayers];
+    const int v = blockIdx.x;
+    for (int l = threadIdx.x; l < L; l += 256) {
+        const int32_t* a = idx + ((size_t)l * S + (size_t)v * window) * k;        // window v of layer l
+        const int32_t* b = a + (size_t)window * k;                                // window v + 1
+        double dot = 0.0, aa = 0.0, bb = 0.0;
+        for (int e = 0; e < E; ++e) {
+            int ca = 0, cb = 0;
+            for (int i = 0; i < window * k; ++i) {
+                ca += a[i] == e ? 1 : 0;
+                cb += b[i] == e ? 1 : 0;
+            }
+            dot += (double)ca * (double)cb;
+            aa += (double)ca * (double)ca;
+            bb += (double)cb * (double)cb;
+        }
+        cosine[l] = (aa > 0.0 && bb > 0.0) ? dot / (sqrt(aa) * sqrt(bb)) : 0.0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = 0.0;
+        for (int l = 0; l < L; ++l) total += cosine[l];
+        out[1 + v] = total / (double)L;
+    }
+}
+
+// out[0] = mean of out[1 .. n_pairs], summed in index order (0 when there is no pair).
+__global__ void window_mean_kernel(int n_pairs, double* __restrict__ out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    double total = 0.0;
+    for (int v = 0; v < n_pairs; ++v) total += out[1 + v];
+    out[0] = n_pairs > 0 ? total / (double)n_pairs : 0.0;
 }
 
 // ---- Algorithm 1 ------------------------------------------------------------------------------
@@ -185,6 +227,21 @@ int daop_similarity(int32_t n_layers, int32_t n_experts, const int32_t* counts_p
     if (counts_p == nullptr || counts_d == nullptr || out == nullptr) return MOE_ERR_NULL;
     if (misaligned16(counts_p) || misaligned16(counts_d) || misaligned16(out)) return MOE_ERR_ALIGN;
     similarity_kernel<<<1, 64, 0, static_cast<hipStream_t>(hip_stream)>>>(n_layers, n_experts, counts_p, counts_d, out);
+    return done();
+}
+
+int daop_window_variation(int32_t n_layers, int32_t n_experts, int32_t steps, int32_t top_k, int32_t window,
+                          const int32_t* idx, double* out, void* hip_stream) {
+    if (int rc = check_dims(n_layers, n_experts)) return rc;
+    if (steps < 0 || steps > (1 << 20) || top_k < 1 || top_k > 8 || top_k > n_experts) return MOE_ERR_SHAPE;
+    if (window < 1 || window > 4096) return MOE_ERR_SHAPE;
+    if (out == nullptr || (steps > 0 && idx == nullptr)) return MOE_ERR_NULL;
+    if (misaligned16(out) || (idx != nullptr && misaligned16(idx))) return MOE_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int n_pairs = steps / window - 1;
+    if (n_pairs > 0)
+        window_pairs_kernel<<<n_pairs, 256, 0, stream>>>(n_layers, n_experts, steps, top_k, window, idx, out);
+    window_mean_kernel<<<1, 64, 0, stream>>>(n_pairs > 0 ? n_pairs : 0, out);
     return done();
 }
 

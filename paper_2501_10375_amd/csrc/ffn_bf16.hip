@@ -59,15 +59,19 @@ __global__ __launch_bounds__(256) void combine_bf16(const float* __restrict__ ou
 template <int BK, int STAGES, bool SKIP, int BT = gg::kBT>
 hipError_t launch_gemms(const moe_shape_t& s, const uint16_t* x, const uint16_t* act_in, const uint16_t* w1,
                         const uint16_t* w3, const uint16_t* w2, const int32_t* offs, const int32_t* row_of_slot,
-                        void* act, float* out, int32_t* sync, float* partial, hipStream_t stream) {
+                        void* act, float* out, int32_t* sync, float* partial, const StaleInput& alt, hipStream_t stream) {
     using G1 = gg::Gemm<2, BK, STAGES, kWT, kWW, SKIP, BT>;
     using G2 = gg::Gemm<1, BK, STAGES, kWT, kWW, SKIP, BT>;
     auto k1 = gg::grouped_gemm_kernel<2, BK, STAGES, kWT, kWW, SKIP, BT>;
     auto k2 = gg::grouped_gemm_kernel<1, BK, STAGES, kWT, kWW, SKIP, BT>;
+    auto k1_alt = gg::grouped_gemm1_alt_kernel<BK, STAGES, kWT, kWW, SKIP, BT>;
     static bool configured = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G1::kLdsBytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1_alt), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                G1::kLdsBytes);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 G2::kLdsBytes);
@@ -76,8 +80,13 @@ hipError_t launch_gemms(const moe_shape_t& s, const uint16_t* x, const uint16_t*
     }
     // One persistent workgroup per CU (a multiple of the 8 XCDs); the kernels size their own work from `offs`.
     const int grid = max(gg::kXcds, compute_units() / gg::kXcds * gg::kXcds);
-    k1<<<grid, G1::kThreads, G1::kLdsBytes, stream>>>(x, w1, w3, offs, row_of_slot, s.n_experts, s.top_k, s.ffn,
-                                                      s.hidden, act, sync, partial);
+    if (alt.stale != nullptr)
+        k1_alt<<<grid, G1::kThreads, G1::kLdsBytes, stream>>>(x, static_cast<const uint16_t*>(alt.x_stale), alt.stale, w1, w3,
+                                                              offs, row_of_slot, s.n_experts, s.top_k, s.ffn, s.hidden, act,
+                                                              sync, partial);
+    else
+        k1<<<grid, G1::kThreads, G1::kLdsBytes, stream>>>(x, w1, w3, offs, row_of_slot, s.n_experts, s.top_k, s.ffn,
+                                                          s.hidden, act, sync, partial);
     stage_mark(stream, kStageGemm1);
     k2<<<grid, G2::kThreads, G2::kLdsBytes, stream>>>(act_in, w2, nullptr, offs, row_of_slot, s.n_experts, s.top_k,
                                                       s.hidden, s.ffn, out, sync + gg::kSyncInts, partial);
@@ -90,7 +99,7 @@ hipError_t launch_gemms(const moe_shape_t& s, const uint16_t* x, const uint16_t*
 hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w, const void* w1,
                            const void* w3, const void* w2, void* y, const int32_t* offs,
                            const int32_t* row_of_slot, const int32_t* slot_of, void* act, float* out,
-                           int32_t* sync, float* partial, hipStream_t stream) {
+                           int32_t* sync, float* partial, const StaleInput& alt, hipStream_t stream) {
     static_assert(gg::kSyncInts == kGemmSyncInts && gg::kScratchBytes == kGemmScratchBytes, "workspace layout");
     const uint16_t* xs = static_cast<const uint16_t*>(x);
     const uint16_t* a16 = static_cast<const uint16_t*>(act);
@@ -102,11 +111,11 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
 #ifndef MOE_GEMM_BT
 #define MOE_GEMM_BT 256
 #endif
-    e = ragged ? launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, true, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream)
-               : launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, false, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+    e = ragged ? launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, true, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream)
+               : launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, false, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream);
 #else
-    e = ragged ? launch_gemms<64, 3, true, 128>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream)
-               : launch_gemms<64, 2, false, 256>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, stream);
+    e = ragged ? launch_gemms<64, 3, true, 128>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream)
+               : launch_gemms<64, 2, false, 256>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream);
 #endif
     if (e != hipSuccess) return e;
     combine_bf16<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, static_cast<uint16_t*>(y));

@@ -127,6 +127,9 @@ struct DecodeArgs {
     const uint16_t* wg_next;
     const float* bias_next;
     int32_t* pred_out;
+    // pre-calculated selections (ALT kernels only): assignment a reads x_stale instead of x when stale[a] != 0
+    const uint16_t* x_stale;
+    const uint8_t* stale;
     const uint16_t *w1, *w3, *w2;
     uint16_t* act;          // [T*k, F] workspace
     uint16_t* y;            // [T, H]
@@ -327,11 +330,19 @@ struct Smem {
     f32x4 red[kRedBufs][kWaves][2][NC][64];
     float yacc[16 * NC][16];
     int failed;               // a rendezvous of this workgroup gave up: its output tiles become NaN
+    unsigned char stale[16 * NC * 8];  // ALT kernels: the call's stale mask, per assignment
 };
 
 // ---- phase 1: act[a, f] = silu(x[t] . w1[e, f]) * (x[t] . w3[e, f]) over this workgroup's share
 // of the (active expert, 16-feature tile) list.
-template <int P, int NC>
+// Row of the token operand of assignment a: x, or x_stale for a pre-calculated selection (ALT).
+template <bool ALT, int NC>
+__device__ inline const uint16_t* token_row(const DecodeArgs& p, const Smem<NC>& sm, int a) {
+    const uint16_t* base = (ALT && sm.stale[a] != 0) ? p.x_stale : p.x;
+    return base + (size_t)(a / p.k) * p.H;
+}
+
+template <int P, int NC, bool ALT>
 __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t epoch, bool& a_open) {
     const Groups<NC>& g = sm.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -356,7 +367,8 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
     u32x4 lo1[P], hi1[P], lo3[P], hi3[P], xa[P][NC], xb[P][NC];
     // Issue-side state: the next step to request and the row bases of its tile.
     int is = 0, itile = t0;
-    size_t wlo = 0, whi = 0, xbase[NC];
+    size_t wlo = 0, whi = 0;
+    const uint16_t* xbase[NC];
     auto enter_tile = [&]() {
         const int d = itile / tiles_per_expert;
         const int f0 = (itile - d * tiles_per_expert) * 16;
@@ -365,7 +377,7 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
         whi = (row0 + lm.row_hi) * H + k0 + lm.k_ld;
 #pragma unroll
         for (int c = 0; c < NC; ++c)  // columns without a token read the expert's first token (result unused)
-            xbase[c] = (size_t)(g.assign[d][col + 16 * c < g.cnt[d] ? col + 16 * c : 0] / k) * H + k0 + lm.kq8;
+            xbase[c] = token_row<ALT, NC>(p, sm, g.assign[d][col + 16 * c < g.cnt[d] ? col + 16 * c : 0]) + k0 + lm.kq8;
     };
     enter_tile();
     auto issue = [&](int i) {  // requests past the last tile re-read it
@@ -376,8 +388,8 @@ __device__ inline void gemm1_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
         hi3[i] = load16(p.w3 + whi + off);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            xa[i][c] = load16(p.x + xbase[c] + off);
-            xb[i][c] = load16(p.x + xbase[c] + off + 32);
+            xa[i][c] = load16(xbase[c] + off);
+            xb[i][c] = load16(xbase[c] + off + 32);
         }
         if (++is == spt) {
             is = 0;
@@ -482,7 +494,7 @@ __device__ inline int phase1_participants(int total_tiles, int grid) {
     const int busiest = (total_tiles + grid - 1) / grid;
     return (total_tiles + busiest - 1) / max(busiest, 1);
 }
-template <int P, int NC>
+template <int P, int NC, bool ALT>
 __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, uint32_t epoch, bool& a_open) {
     static_assert(kXSteps % P == 0, "the weight ring must divide a tile");
     const Groups<NC>& g = sm.g;
@@ -559,7 +571,7 @@ __device__ inline void gemm1_phase_xreg(const DecodeArgs& p, Smem<NC>& sm, uint3
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 // columns without a token read the expert's first token (their results are unused)
-                const uint16_t* xp = p.x + (size_t)(g.assign[d][col + 16 * c < cnt ? col + 16 * c : 0] / k) * H + k0 + lm.kq8;
+                const uint16_t* xp = token_row<ALT, NC>(p, sm, g.assign[d][col + 16 * c < cnt ? col + 16 * c : 0]) + k0 + lm.kq8;
 #pragma unroll
                 for (int s = 0; s < kXSteps; ++s) {
                     const size_t off = (size_t)(s < n_valid ? s : 0) * kstride;
@@ -776,9 +788,10 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
 // The whole MoE layer of a decode-size call in one launch (NC = 1, ROUTE), or the expert FFN of a
 // call of up to 16 * NC tokens whose selections were made earlier.  Every workgroup must be
 // resident at the same time (grid <= number of compute units, one 512-thread workgroup each).
-template <int P1, int P2, bool ROUTE, int NC>
+template <int P1, int P2, bool ROUTE, int NC, bool ALT = false>
 __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     static_assert(!ROUTE || NC == 1, "in-kernel routing serves at most 16 tokens");
+    static_assert(!(ROUTE && ALT), "pre-calculated selections come with their routing");
     __shared__ Smem<NC> sm;
     const int tid = threadIdx.x;
     const int A = p.T * p.k;
@@ -819,6 +832,7 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
         for (int i = tid; i < A; i += kThreads) {
             sm.idx[i] = p.idx_in[i];
             sm.w[i] = p.w_in[i];
+            if (ALT) sm.stale[i] = p.stale[i];
         }
     }
     __syncthreads();
@@ -828,8 +842,8 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     const uint32_t count = (uint32_t)__builtin_amdgcn_readfirstlane((int)last_count) + 1u;
     const uint32_t epoch = count ^ 0x9E3779B9u;
     bool a_open = true;  // flag A not raised yet
-    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC>(p, sm, epoch, a_open);
-    else gemm1_phase<P1, NC>(p, sm, epoch, a_open);
+    if (p.H <= 64 * kXSteps * kWaves) gemm1_phase_xreg<P1, NC, ALT>(p, sm, epoch, a_open);
+    else gemm1_phase<P1, NC, ALT>(p, sm, epoch, a_open);
     gemm2_phase<P2, NC>(p, sm, epoch, a_open);
     if (blockIdx.x == 0 && tid == 0)  // the next launch counts on from here
         __hip_atomic_store(&p.flags[kEpochIndex], count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -849,8 +863,11 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
 
 hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
                                const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
-                               const void* w2, void* y, void* act, uint32_t* flags, hipStream_t stream) {
+                               const void* w2, void* y, void* act, uint32_t* flags, const StaleInput& alt,
+                               hipStream_t stream) {
     DecodeArgs p{};
+    p.x_stale = static_cast<const uint16_t*>(alt.x_stale);
+    p.stale = alt.stale;
     p.x = static_cast<const uint16_t*>(x);
     if (route != nullptr) {
         p.wg = static_cast<const uint16_t*>(route->w_gate);
@@ -882,6 +899,9 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     const int grid = min(min(compute_units(), kFlagStride), max(max_tiles1, s.hidden / 16));
     if (route != nullptr) {
         decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, true, 1><<<grid, kThreads, 0, stream>>>(p);
+    } else if (alt.stale != nullptr) {
+        if (tokens <= 16) decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 1, true><<<grid, kThreads, 0, stream>>>(p);
+        else decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 2, true><<<grid, kThreads, 0, stream>>>(p);
     } else if (tokens <= 16) {
         decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 1><<<grid, kThreads, 0, stream>>>(p);
     } else {

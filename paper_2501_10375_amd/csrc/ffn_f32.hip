@@ -47,7 +47,9 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_f32(const float* __restrict_
                                                         const float* __restrict__ w3,
                                                         const int32_t* __restrict__ offs,
                                                         const int32_t* __restrict__ row_of_slot, int E, int k, int H,
-                                                        int F, float* __restrict__ act) {
+                                                        int F, float* __restrict__ act,
+                                                        const float* __restrict__ x_stale,
+                                                        const uint8_t* __restrict__ stale) {
     __shared__ float As[BK][BM + 4];
     __shared__ float B1s[BK][BN + 4];
     __shared__ float B3s[BK][BN + 4];
@@ -57,8 +59,10 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_f32(const float* __restrict_
     const int tid = threadIdx.x;
     const int lr = tid >> 2, kq = tid & 3;  // staging: row 0..63, k quarter 0..3
     const int srow = min(lr, rows - 1);     // rows past the end re-read a valid row; never stored
-    const int token = row_of_slot[slot0 + srow] / k;
-    const float* xa = x + (size_t)token * H;
+    const int assignment = row_of_slot[slot0 + srow];  // t * k + j
+    const int token = assignment / k;
+    // a pre-calculated selection reads the earlier hidden state of its token
+    const float* xa = ((stale != nullptr && stale[assignment] != 0) ? x_stale : x) + (size_t)token * H;
     const float* b1 = w1 + ((size_t)e * F + f0 + lr) * H;
     const float* b3 = w3 + ((size_t)e * F + f0 + lr) * H;
     const int tm = (tid >> 4) * 4, tn = (tid & 15) * 4;
@@ -166,11 +170,12 @@ __global__ __launch_bounds__(256) void combine_f32(const float* __restrict__ out
 hipError_t launch_ffn_f32(const moe_shape_t& s, int tokens, const float* x, const float* topk_w, const float* w1,
                           const float* w3, const float* w2, float* y, const int32_t* offs,
                           const int32_t* row_of_slot, const int32_t* slot_of, float* act, float* out,
-                          hipStream_t stream) {
+                          const StaleInput& alt, hipStream_t stream) {
     const int A = tokens * s.top_k;
     const int max_mtiles = (A + BM - 1) / BM + s.n_experts;
     gemm1_swiglu_f32<<<dim3(max_mtiles, s.ffn / BN), 256, 0, stream>>>(x, w1, w3, offs, row_of_slot, s.n_experts,
-                                                                       s.top_k, s.hidden, s.ffn, act);
+                                                                       s.top_k, s.hidden, s.ffn, act,
+                                                                       static_cast<const float*>(alt.x_stale), alt.stale);
     stage_mark(stream, kStageGemm1);
     gemm2_f32<<<dim3(max_mtiles, s.hidden / BN), 256, 0, stream>>>(act, w2, offs, s.n_experts, s.hidden, s.ffn,
                                                                   out);

@@ -156,8 +156,11 @@ struct Swz<32> {  // 64-byte rows, 4 pieces; four rows span the 64 banks
 // SKIP: slot fragments of a ragged tile that hold no valid slot are skipped (their LDS reads and
 // MFMAs).  That pays when many experts are cold (most tiles ragged), but it puts every MFMA behind a
 // scalar branch, which costs a little when nearly all tiles are full; the launcher decides.
-template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT>
+// ALT (gemm1 only): a slot's row comes from `tok_alt` instead of `tok_base` when alt_mask[assignment]
+// is set: expert execution with some selections pre-calculated on an earlier hidden state.
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT, bool ALT = false>
 struct Gemm {
+    static_assert(!ALT || NMAT == 2, "only the first GEMM gathers rows of x");
     static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
     static constexpr int kThreads = kWaves * 64;
     static_assert(BT % (32 * WT) == 0 && BT <= kBT, "slot tile height");
@@ -201,7 +204,9 @@ struct Gemm {
                                       const uint16_t* __restrict__ wb, const int32_t* __restrict__ offs,
                                       const int32_t* __restrict__ row_of_slot, int E, int topk, int N, int K,
                                       void* __restrict__ dst, int32_t* __restrict__ sync,
-                                      float* __restrict__ scratch, unsigned char* lds) {
+                                      float* __restrict__ scratch, unsigned char* lds,
+                                      const uint16_t* __restrict__ tok_alt = nullptr,
+                                      const uint8_t* __restrict__ alt_mask = nullptr) {
         const int n_ftiles = (N + kBF - 1) / kBF;
         const int total = count_tiles(offs, E, n_ftiles, BT);
         const int KT = K / BK;
@@ -232,7 +237,7 @@ struct Gemm {
             const int kt0 = (int)((long)KT * part / p), kt1 = (int)((long)KT * (part + 1) / p);
             tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft, kt0, kt1, p, part,
                  scratch + ((size_t)xcd * kMaxWgsPerXcd + (size_t)t * p) * kPartialFloats,
-                 sync + kXcds + xcd * kMaxWgsPerXcd + t);
+                 sync + kXcds + xcd * kMaxWgsPerXcd + t, tok_alt, alt_mask);
         }
     }
 
@@ -243,7 +248,8 @@ struct Gemm {
                                 const uint16_t* __restrict__ wb, const int32_t* __restrict__ row_of_slot, int topk,
                                 int N, int K, void* __restrict__ dst, unsigned char* lds, int e, int slot0, int rows,
                                 int ft, int kt_begin, int kt_end, int parts, int part, float* __restrict__ partials,
-                                int32_t* __restrict__ arrivals) {
+                                int32_t* __restrict__ arrivals, const uint16_t* __restrict__ tok_alt,
+                                const uint8_t* __restrict__ alt_mask) {
         const int n0 = ft * kBF;
         const int tid = threadIdx.x, lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
@@ -261,8 +267,10 @@ struct Gemm {
             const int r = wave * kTokStageRows + q * kRowsPerLoad + lrow;  // row in the slot tile
             const int chunk = Swz<BK>::piece(r, lpiece);        // global piece that belongs at this position
             const int slot = slot0 + min(r, rows - 1);          // rows past the end re-read the last valid row
-            const int src = (NMAT == 2) ? row_of_slot[slot] / topk : slot;
-            gp[q] = reinterpret_cast<const char*>(tok_base + (size_t)src * K) + chunk * 16 + k_first;
+            const int assignment = (NMAT == 2) ? row_of_slot[slot] : 0;   // t * topk + j
+            const int src = (NMAT == 2) ? assignment / topk : slot;
+            const uint16_t* rows_from = (ALT && alt_mask[assignment] != 0) ? tok_alt : tok_base;
+            gp[q] = reinterpret_cast<const char*>(rows_from + (size_t)src * K) + chunk * 16 + k_first;
         }
 #pragma unroll
         for (int q = 0; q < kLoadsPerOperand; ++q) {
@@ -526,6 +534,18 @@ __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uin
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
     Gemm<NMAT, BK, STAGES, WT, WW, SKIP, BT>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
                                                lds_dyn);
+}
+
+// gemm1 with per-selection input rows (see Gemm's ALT).
+template <int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT>
+__global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm1_alt_kernel(
+    const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ tok_alt, const uint8_t* __restrict__ alt_mask,
+    const uint16_t* __restrict__ wa, const uint16_t* __restrict__ wb, const int32_t* __restrict__ offs,
+    const int32_t* __restrict__ row_of_slot, int E, int topk, int N, int K, void* __restrict__ dst,
+    int32_t* __restrict__ sync, float* __restrict__ scratch) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
+    Gemm<2, BK, STAGES, WT, WW, SKIP, BT, true>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync,
+                                                            scratch, lds_dyn, tok_alt, alt_mask);
 }
 
 }  // namespace gg

@@ -200,16 +200,34 @@ hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* 
     return e;
 }
 
+constexpr StaleInput kNoStaleInput = {nullptr, nullptr};
+
 hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_t* idx, const float* w,
-                   const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream) {
+                   const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream,
+                   const StaleInput& alt = kNoStaleInput) {
     if (stream_path(s, tokens))
-        return launch_decode_layer(s, tokens, x, nullptr, idx, w, w1, w3, w2, y, ws.act, ws.dec_flags, stream);
+        return launch_decode_layer(s, tokens, x, nullptr, idx, w, w1, w3, w2, y, ws.act, ws.dec_flags, alt, stream);
     if (s.dtype == MOE_F32)
         return launch_ffn_f32(s, tokens, static_cast<const float*>(x), w, static_cast<const float*>(w1),
                               static_cast<const float*>(w3), static_cast<const float*>(w2), static_cast<float*>(y),
-                              ws.offs, ws.row_of_slot, ws.slot_of, static_cast<float*>(ws.act), ws.out, stream);
+                              ws.offs, ws.row_of_slot, ws.slot_of, static_cast<float*>(ws.act), ws.out, alt, stream);
     return launch_ffn_bf16(s, tokens, x, w, w1, w3, w2, y, ws.offs, ws.row_of_slot, ws.slot_of, ws.act, ws.out,
-                           ws.sync, ws.partial, stream);
+                           ws.sync, ws.partial, alt, stream);
+}
+
+// Expert execution on a carved workspace from selections made earlier (arguments already checked).
+int enqueue_expert_ffn(const moe_shape_t& s, int32_t tokens, const void* x, const int32_t* topk_idx, const float* topk_w,
+                       const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream,
+                       const StaleInput& alt) {
+    stage_call_begin(stream);
+    if (!stream_path(s, tokens)) {
+        hipError_t e = launch_hist_from_idx(s, tokens, topk_idx, ws.hist, stream);
+        if (e != hipSuccess) return MOE_ERR_DEVICE;
+        e = launch_finalize(s, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, ws.sync, stream);
+        stage_mark(stream, kStagePermute);
+        if (e != hipSuccess) return MOE_ERR_DEVICE;
+    }
+    return dev(run_ffn(s, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream, alt));
 }
 
 
@@ -240,7 +258,8 @@ int enqueue_layer(const moe_shape_t& s, int32_t tokens, const void* x, const voi
         // One kernel routes, runs the experts and (in one of its workgroups, at the end) evaluates the
         // prediction gate.
         const DecodeRoute r = {w_gate, gate_bias, topk_idx, topk_w, counts, accumulate, w_gate_next, gate_bias_next, pred_idx};
-        return dev(launch_decode_layer(s, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags, stream));
+        return dev(launch_decode_layer(s, tokens, x, &r, nullptr, nullptr, w1, w3, w2, y, ws.act, ws.dec_flags, kNoStaleInput,
+                                       stream));
     }
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;
@@ -345,17 +364,26 @@ int moe_expert_ffn(const moe_shape_t* shape, int32_t tokens, const void* x, cons
     const WorkspaceLayout L = workspace_layout(*shape, tokens);
     if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
     if (tokens == 0) return MOE_OK;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const Ws ws = carve(workspace, L);
-    stage_call_begin(stream);
-    if (!stream_path(*shape, tokens)) {
-        hipError_t e = launch_hist_from_idx(*shape, tokens, topk_idx, ws.hist, stream);
-        if (e != hipSuccess) return MOE_ERR_DEVICE;
-        e = launch_finalize(*shape, tokens, ws.hist, topk_idx, nullptr, 0, ws.offs, ws.row_of_slot, ws.slot_of, ws.sync, stream);
-        stage_mark(stream, kStagePermute);
-        if (e != hipSuccess) return MOE_ERR_DEVICE;
-    }
-    return dev(run_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+    return enqueue_expert_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, carve(workspace, L),
+                              static_cast<hipStream_t>(hip_stream), kNoStaleInput);
+}
+
+int moe_expert_ffn_precalc(const moe_shape_t* shape, int32_t tokens, const void* x, const void* x_stale,
+                           const uint8_t* stale, const int32_t* topk_idx, const float* topk_w, const void* w1,
+                           const void* w3, const void* w2, void* y, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
+    if (int rc = check_shape(shape)) return rc;
+    if (tokens < 0 || tokens > kMaxTokens) return MOE_ERR_SHAPE;
+    const void* const req[] = {w1, w3, w2, workspace};
+    if (int rc = check_required(req)) return rc;
+    const void* const per_token[] = {x, x_stale, stale, topk_idx, topk_w, y};
+    if (int rc = tokens > 0 ? check_required(per_token) : check_optional(per_token)) return rc;
+    const WorkspaceLayout L = workspace_layout(*shape, tokens);
+    if (workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    if (tokens == 0) return MOE_OK;
+    const StaleInput alt = {x_stale, stale};
+    return enqueue_expert_ffn(*shape, tokens, x, topk_idx, topk_w, w1, w3, w2, y, carve(workspace, L),
+                              static_cast<hipStream_t>(hip_stream), alt);
 }
 
 int moe_layer(const moe_shape_t* shape, int32_t tokens, const void* x, const void* w_gate, const float* gate_bias,

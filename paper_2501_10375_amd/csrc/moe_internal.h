@@ -100,17 +100,25 @@ hipError_t launch_route_small(const moe_shape_t& s, int tokens, const void* x, c
                               int n_gates, int32_t* counts, int accumulate, int32_t* counts_next,
                               hipStream_t stream);
 
+// Expert execution with pre-calculated selections (moe_expert_ffn_precalc): selection a = t * k + j
+// reads its input row from x_stale instead of x when stale[a] != 0.  Both null: the plain layer.
+struct StaleInput {
+    const void* x_stale;   // [T, H], storage type of x
+    const uint8_t* stale;  // [T, k]
+};
+
 // Grouped expert FFN, fp32 storage.
 hipError_t launch_ffn_f32(const moe_shape_t& s, int tokens, const float* x, const float* topk_w,
                           const float* w1, const float* w3, const float* w2, float* y,
                           const int32_t* offs, const int32_t* row_of_slot, const int32_t* slot_of,
-                          float* act, float* out, hipStream_t stream);
+                          float* act, float* out, const StaleInput& alt, hipStream_t stream);
 
 // Grouped expert FFN, bf16 storage, MFMA (prefill-size calls).
 hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, const float* topk_w,
                            const void* w1, const void* w3, const void* w2, void* y,
                            const int32_t* offs, const int32_t* row_of_slot, const int32_t* slot_of,
-                           void* act, float* out, int32_t* sync, float* partial, hipStream_t stream);
+                           void* act, float* out, int32_t* sync, float* partial, const StaleInput& alt,
+                           hipStream_t stream);
 
 // Number of compute units of the current device (cached per device).
 int compute_units();
@@ -142,6 +150,7 @@ struct DecodeRoute {
 };
 hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
                                const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
-                               const void* w2, void* y, void* act, uint32_t* flags, hipStream_t stream);
+                               const void* w2, void* y, void* act, uint32_t* flags, const StaleInput& alt,
+                               hipStream_t stream);
 
 }  // namespace moe

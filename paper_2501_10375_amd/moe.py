@@ -25,7 +25,7 @@ STATUS = {0: "MOE_OK", -1: "MOE_ERR_NULL", -2: "MOE_ERR_SHAPE", -3: "MOE_ERR_DTY
           -5: "MOE_ERR_ALIGN", -6: "MOE_ERR_DEVICE", -7: "MOE_ERR_TOO_LARGE"}
 
 EXPORTS = ("moe_status_string", "moe_workspace_bytes", "moe_route_workspace_bytes", "moe_route",
-           "moe_predict_next", "moe_expert_ffn", "moe_layer", "moe_layer_static", "moe_decode_status",
+           "moe_predict_next", "moe_expert_ffn", "moe_expert_ffn_precalc", "moe_layer", "moe_layer_static", "moe_decode_status",
            # include/moe_measure.h
            "moe_stage_timing_begin", "moe_stage_timing_end", "moe_calibrate_mfma", "moe_calibrate_read_stream",
            "moe_measure_set_decode_spin_limit")
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.moe_predict_next.restype = ctypes.c_int
         L.moe_expert_ffn.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.moe_expert_ffn.restype = ctypes.c_int
+        L.moe_expert_ffn_precalc.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.moe_expert_ffn_precalc.restype = ctypes.c_int
         L.moe_layer.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.moe_layer.restype = ctypes.c_int
         L.moe_layer_static.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
@@ -173,6 +175,19 @@ def moe_expert_ffn(shape: MoeShape, x, topk_idx, topk_w, w1, w3, w2, y, workspac
                                 _p(w3, dt, (E, F, H), "w3"), _p(w2, dt, (E, H, F), "w2"), _p(y, dt, (T, H), "y"),
                                 _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()),
            "moe_expert_ffn")
+
+
+def moe_expert_ffn_precalc(shape: MoeShape, x, x_stale, stale, topk_idx, topk_w, w1, w3, w2, y, workspace):
+    """moe_expert_ffn where selection (t, j) is evaluated on x_stale[t] if stale[t, j] (uint8) is non-zero."""
+    T, E, k, H, F = x.shape[0], shape.n_experts, shape.top_k, shape.hidden, shape.ffn
+    dt = x.dtype
+    _check(lib().moe_expert_ffn_precalc(ctypes.byref(shape), T, _p(x, None, (T, H), "x"), _p(x_stale, dt, (T, H), "x_stale"),
+                                        _p(stale, torch.uint8, (T, k), "stale"),
+                                        _p(topk_idx, torch.int32, (T, k), "topk_idx"),
+                                        _p(topk_w, torch.float32, (T, k), "topk_w"), _p(w1, dt, (E, F, H), "w1"),
+                                        _p(w3, dt, (E, F, H), "w3"), _p(w2, dt, (E, H, F), "w2"), _p(y, dt, (T, H), "y"),
+                                        _p(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream()),
+           "moe_expert_ffn_precalc")
 
 
 def moe_layer(shape: MoeShape, x, w_gate, gate_bias, w_gate_next, gate_bias_next, w1, w3, w2, y, topk_idx, topk_w,

@@ -12,7 +12,7 @@ import torch
 from . import moe
 from .moe import _check, _p, _stream
 
-EXPORTS = ("daop_similarity", "daop_plan_swaps", "daop_memory_init", "daop_predict_degraded")
+EXPORTS = ("daop_similarity", "daop_window_variation", "daop_plan_swaps", "daop_memory_init", "daop_predict_degraded")
 _ready = False
 
 
@@ -22,6 +22,7 @@ def lib() -> ctypes.CDLL:
     if not _ready:
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         L.daop_similarity.argtypes = [i32, i32, vp, vp, vp, vp]
+        L.daop_window_variation.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp]
         L.daop_plan_swaps.argtypes = [i32, i32, vp, vp, ctypes.c_double, vp, vp, vp]
         L.daop_memory_init.argtypes = [i32, i32, vp, i32, vp, vp]
         L.daop_predict_degraded.argtypes = [ctypes.POINTER(moe.MoeShape), i32, vp, vp, vp, vp, vp, vp, vp]
@@ -38,6 +39,17 @@ def daop_similarity(counts_p: torch.Tensor, counts_d: torch.Tensor):
     _check(lib().daop_similarity(L, E, _p(counts_p, torch.int32, (L, E), "counts_p"),
                                  _p(counts_d, torch.int32, (L, E), "counts_d"), _p(out), _stream()), "daop_similarity")
     return out[0], out[1:]
+
+
+def daop_window_variation(idx: torch.Tensor, n_experts: int, window: int = 15):
+    """Sec. VI-B on int32 [L, S, k] selections of S decode steps.  Returns (mean similarity of consecutive
+    windows, per-pair similarities) as fp64 tensors on the GPU."""
+    L, S, k = idx.shape
+    n_pairs = max(S // window - 1, 0)
+    out = torch.empty(2 + n_pairs, dtype=torch.float64, device=idx.device)   # one spare element keeps it non-empty
+    _check(lib().daop_window_variation(L, n_experts, S, k, int(window), _p(idx, torch.int32, (L, S, k), "idx"), _p(out),
+                                       _stream()), "daop_window_variation")
+    return out[0], out[1:1 + n_pairs]
 
 
 def daop_plan_swaps(counts: torch.Tensor, on_gpu: torch.Tensor, swap_in_out: float = 1.05):

@@ -119,7 +119,7 @@ def agreement(pred: torch.Tensor, actual: torch.Tensor):
 def forward_precalc(st: MoeStack, h0: torch.Tensor, on_gpu: torch.Tensor, first_predicted_layer: int = 5,
                     keep_layers: bool = False):
     """The decode-phase approximation of DAOP (Sec. IV-C) on the stack, for measuring what it does
-    to the outputs (not a fast path: it costs two expert passes per layer).
+    to the outputs.
 
     on_gpu: uint8 [L, E] expert cache.  Layers below `first_predicted_layer` run exactly (the paper
     uses the original gate for the first blocks: prediction for block i + 1 is applied when i >= 4).
@@ -127,7 +127,7 @@ def forward_precalc(st: MoeStack, h0: torch.Tensor, on_gpu: torch.Tensor, first_
     u_{l-1} with layer l's gate, gracefully degraded against the cache (`daop_predict_degraded`),
     with the predicted weights; a selected expert that is outside the cache is evaluated on the stale
     input u_{l-1} (it was pre-calculated one layer ahead), one inside the cache on the true input
-    u_l.  Returns the final hidden state (fp32) and the number of (token, selection) pairs evaluated
+    u_l (one `moe_expert_ffn_precalc` call per layer).  Returns the final hidden state (fp32) and the number of (token, selection) pairs evaluated
     on stale input; with keep_layers also the per-layer (u_prev, u, idx, w, stale mask, y).
     """
     from . import policy
@@ -138,7 +138,6 @@ def forward_precalc(st: MoeStack, h0: torch.Tensor, on_gpu: torch.Tensor, first_
     w = torch.empty((T, k), dtype=torch.float32, device=dev)
     counts = torch.zeros((st._epad,), dtype=torch.int32, device=dev)
     y = torch.empty((T, st.H), dtype=dt, device=dev)
-    y2 = torch.empty((T, st.H), dtype=dt, device=dev)
     h = h0
     u_prev = None
     n_stale = 0
@@ -153,14 +152,9 @@ def forward_precalc(st: MoeStack, h0: torch.Tensor, on_gpu: torch.Tensor, first_
         else:
             row = on_gpu[l].clone()   # its own allocation: the library wants 16-byte aligned pointers
             policy.daop_predict_degraded(st.shape, u_prev, d["wg"], d["bias"], row, idx, w)
-            stale = row[idx.long()] == 0                       # [T, k]: selected expert is outside the cache
-            w_fresh = torch.where(stale, torch.zeros_like(w), w)
-            w_stale = torch.where(stale, w, torch.zeros_like(w))
-            moe.moe_expert_ffn(st.shape, u, idx, w_fresh, d["w1"], d["w3"], d["w2"], y, st.workspace)
+            stale = (row[idx.long()] == 0).to(torch.uint8)     # [T, k]: selected expert is outside the cache
+            moe.moe_expert_ffn_precalc(st.shape, u, u_prev, stale, idx, w, d["w1"], d["w3"], d["w2"], y, st.workspace)
             out = y.float()
-            if bool(stale.any()):
-                moe.moe_expert_ffn(st.shape, u_prev, idx, w_stale, d["w1"], d["w3"], d["w2"], y2, st.workspace)
-                out = out + y2.float()
             n_stale += int(stale.sum().item())
         if keep_layers:
             layers.append((u_prev, u, idx.clone(), w.clone(), None if stale is None else stale.clone(), out.clone()))

@@ -45,7 +45,7 @@ def test_library_exports_every_declared_symbol(L):
     from paper_2501_10375_amd import policy
 
     declared = _declared_functions(POLICY_HEADER, "daop_")
-    assert len(declared) == 4
+    assert len(declared) == 5
     for name in declared:
         assert hasattr(L, name), name
     assert set(policy.EXPORTS) == set(declared)
@@ -60,6 +60,10 @@ def test_policy_calls_reject_bad_arguments_on_the_host(L):
     assert P.daop_similarity(4, 65, fake, fake, fake, None) == moe.MOE_ERR_SHAPE
     assert P.daop_similarity(4, 8, None, fake, fake, None) == moe.MOE_ERR_NULL
     assert P.daop_similarity(4, 8, ctypes.c_void_p(0x1004), fake, fake, None) == moe.MOE_ERR_ALIGN
+    assert P.daop_window_variation(4, 8, 60, 2, 0, fake, fake, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_window_variation(4, 8, 60, 9, 15, fake, fake, None) == moe.MOE_ERR_SHAPE
+    assert P.daop_window_variation(4, 8, 60, 2, 15, None, fake, None) == moe.MOE_ERR_NULL
+    assert P.daop_window_variation(4, 8, 60, 2, 15, fake, ctypes.c_void_p(0x1008), None) == moe.MOE_ERR_ALIGN
     assert P.daop_plan_swaps(4, 8, fake, fake, -1.0, None, None, None) == moe.MOE_ERR_SHAPE
     assert P.daop_plan_swaps(4, 8, fake, fake, float("nan"), None, None, None) == moe.MOE_ERR_SHAPE
     assert P.daop_plan_swaps(4, 8, fake, None, 1.05, None, None, None) == moe.MOE_ERR_NULL

@@ -219,6 +219,51 @@ def test_decode_rendezvous_reports_when_it_gives_up(oracle):
     print(r)
 
 
+@pytest.mark.parametrize("T,H,F,E,k,dtype", [
+    (1, 256, 512, 8, 2, torch.bfloat16), (8, 512, 1024, 8, 2, torch.bfloat16), (16, 128, 320, 8, 8, torch.bfloat16),
+    (24, 256, 512, 8, 2, torch.bfloat16),      # two column groups of the streaming kernel
+    (6, 8192, 128, 8, 2, torch.bfloat16),      # hidden size past the register-resident token operand
+    (300, 256, 512, 8, 2, torch.bfloat16),     # ragged 128-slot tiles
+    (1100, 256, 512, 2, 2, torch.bfloat16),    # full 256-slot tiles, split-K round
+    (64, 256, 512, 8, 2, torch.float32), (5, 64, 128, 4, 2, torch.float32),
+])
+def test_expert_ffn_with_precalculated_selections(oracle, T, H, F, E, k, dtype):
+    """Sec. IV-C pre-calculation as one library call: selections flagged stale are evaluated on an
+    earlier hidden state, the rest on the true input, in one pass over the weights.  Compared with the
+    oracle's definition at the layer's own tolerance; an all-zero mask must equal moe_expert_ffn."""
+    d = synth.moe_layer_inputs(T, H, F, E, dtype, DEV, seed=31, zipf_s=1.2, with_next=False)
+    x_stale = synth.normal((T, H), 4242, synth.TID_X, 1.0, dtype, DEV)
+    shape = moe.make_shape(H, F, E, k, dtype)
+    ws = moe.alloc_workspace(shape, T)
+    idx = torch.empty((T, k), dtype=torch.int32, device=DEV)
+    w = torch.empty((T, k), dtype=torch.float32, device=DEV)
+    counts = torch.zeros((E,), dtype=torch.int32, device=DEV)
+    moe.moe_route(shape, d["x"], d["wg"], d["bias"], idx, w, counts, False, ws)
+    g = torch.Generator(device="cpu").manual_seed(T * 7 + H)
+    stale = (torch.rand((T, k), generator=g) < 0.4).to(torch.uint8)
+    stale[0, 0] = 1
+    if k > 1:
+        stale[0, 1] = 0
+    stale = stale.to(DEV)
+    y = torch.empty((T, H), dtype=dtype, device=DEV)
+    moe.moe_expert_ffn_precalc(shape, d["x"], x_stale, stale, idx, w, d["w1"], d["w3"], d["w2"], y, ws)
+    torch.cuda.synchronize()
+    h = host(dict(d, x_stale=x_stale))
+    ref = oracle.expert_ffn_precalc(h["x"], h["x_stale"], stale.cpu().numpy(), idx.cpu().numpy(),
+                                    w.cpu().numpy().astype(np.float64), h["w1"], h["w3"], h["w2"])
+    err = output_error(to_f64(y), ref)
+    print("precalc", T, H, F, E, k, dtype, "err", err)
+    assert err <= {torch.bfloat16: 2e-2, torch.float32: 1e-4}[dtype]
+    # the mask matters: the plain call differs where a selection is stale
+    y_plain = torch.empty_like(y)
+    moe.moe_expert_ffn(shape, d["x"], idx, w, d["w1"], d["w3"], d["w2"], y_plain, ws)
+    y_zero = torch.empty_like(y)
+    moe.moe_expert_ffn_precalc(shape, d["x"], x_stale, torch.zeros_like(stale), idx, w, d["w1"], d["w3"], d["w2"], y_zero, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y_zero.view(torch.uint8), y_plain.view(torch.uint8))
+    assert not torch.equal(y[0], y_plain[0])
+
+
 def test_prepared_call_equals_run_layer():
     """The binding's pre-marshalled call object enqueues the same call as run_layer."""
     T, H, F, E, k, dtype = 6, 256, 512, 8, 2, torch.bfloat16

@@ -35,6 +35,38 @@ def test_similarity_matches_eq1_oracle(L, E):
     assert abs(same.item() - nz) < 1e-14      # identical patterns: 1 per layer that saw tokens
 
 
+@pytest.mark.parametrize("L,E,k,S,W", [(32, 8, 2, 128, 15), (32, 16, 2, 100, 15), (3, 64, 8, 47, 5), (1, 3, 1, 6, 2),
+                                       (300, 7, 3, 31, 15), (4, 8, 2, 29, 15), (4, 8, 2, 14, 15), (2, 8, 2, 0, 15)])
+def test_window_variation_matches_oracle(L, E, k, S, W):
+    """Sec. VI-B: Eq. 1 between consecutive decode windows, bit for bit up to the rounding of the
+    roots and quotients (the counts and their products are exact on both sides)."""
+    from oracle import daop_policy as pol
+
+    rng = np.random.default_rng(L * 1000 + E * 10 + S)
+    # a drifting skew, so the windows differ by a realistic amount
+    idx = np.zeros((L, S, k), dtype=np.int32)
+    for l in range(L):
+        for s in range(S):
+            p = np.exp(-0.4 * ((np.arange(E) + s // 9 + l) % E))
+            idx[l, s] = rng.choice(E, size=k, replace=False, p=p / p.sum())
+    mean, per = policy.daop_window_variation(torch.from_numpy(idx).to(DEV), E, W)
+    torch.cuda.synchronize()
+    ref_mean, ref_per = pol.window_variation(idx, E, W)
+    assert per.shape[0] == ref_per.shape[0] == max(S // W - 1, 0)
+    assert np.allclose(per.cpu().numpy(), ref_per, rtol=0, atol=4e-16 * max(1, L) ** 0.5 + 1e-15)
+    assert abs(mean.item() - ref_mean) <= 1e-15 * max(1, per.shape[0]) + 1e-15
+    if S // W >= 2:
+        assert 0.0 < ref_mean <= 1.0 + 1e-15
+
+
+def test_window_variation_hand_worked_on_the_gpu():
+    idx = torch.tensor([[[0], [0], [1], [0], [2], [1]]], dtype=torch.int32, device=DEV)
+    mean, per = policy.daop_window_variation(idx, 3, 2)
+    torch.cuda.synchronize()
+    assert abs(per[0].item() - 2 / (2 * 2 ** 0.5)) < 1e-15 and abs(per[1].item() - 0.5) < 1e-15
+    assert abs(mean.item() - (per[0].item() + per[1].item()) / 2) < 1e-15
+
+
 @pytest.mark.parametrize("L,E,thr", [(32, 8, 1.05), (32, 16, 1.05), (7, 64, 1.05), (9, 5, 1.0), (4, 2, 1.05),
                                      (3, 1, 1.05), (16, 8, 0.0), (16, 8, 1e9)])
 def test_plan_swaps_matches_algorithm1_oracle(L, E, thr):
