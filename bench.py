@@ -42,6 +42,15 @@ def parse():
     ap.add_argument("--model", default="mixtral", choices=sorted(WORKLOADS))
     ap.add_argument("--tokens", type=int, default=4096, help="tokens of the headline (prefill) workload")
     ap.add_argument("--decode-tokens", type=int, nargs="*", default=[1, 8, 32], help="decode batch sizes also timed")
+    ap.add_argument("--prefill-tokens", type=int, nargs="*", default=[512, 2048],
+                    help="other prefill lengths of the same layer also timed")
+    ap.add_argument("--other-model", default="phi", choices=sorted(WORKLOADS) + [""],
+                    help="second model shape also timed (prefill and decode); empty string to skip")
+    ap.add_argument("--other-prefill", type=int, default=2048)
+    ap.add_argument("--other-decode-tokens", type=int, nargs="*", default=[1])
+    ap.add_argument("--with-stack", action="store_true", default=None,
+                    help="also run the resident stack of layers (default: only in a run with no workload options)")
+    ap.add_argument("--no-stack", dest="with_stack", action="store_false")
     ap.add_argument("--decode-layers", type=int, default=4,
                     help="distinct weight sets the decode loop rotates over (keeps the weights cold in cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -55,11 +64,15 @@ def parse():
     ap.add_argument("--stack-layers", type=int, default=32)
     ap.add_argument("--stack-prefill", type=int, default=1024)
     ap.add_argument("--stack-decode-steps", type=int, default=128)
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.with_stack is None:   # the stack leg belongs to the default headline run
+        args.with_stack = args.model == "mixtral" and args.tokens == 4096 and args.workload == "layer"
+    return args
 
 
-def run_stack(args):
-    """32 resident Mixtral-shaped layers: prefill of one sequence, then decode steps of one token."""
+def run_stack(args, brief=False):
+    """32 resident Mixtral-shaped layers: prefill of one sequence, then decode steps of one token.
+    brief: leave out the graph replay and the pre-calculation study (the default run's stack leg)."""
     import torch
     from paper_2501_10375_amd import moe, policy, stack, synth
 
@@ -102,20 +115,25 @@ def run_stack(args):
 
     st.forward(hs[0], st.new_counts())
     _, d_wall, d_gpu_ms = timed(decode_loop, L * steps)
-    # the same steps replayed from one HIP graph per step (no per-stage events inside a graph, so wall time only)
-    graph_counts = st.new_counts()
-    step = stack.CapturedStep(st, 1, graph_counts)
-    step.h_in.copy_(hs[0])
-    step.replay()
-    graph_counts.zero_()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for h in hs:
-        step.h_in.copy_(h)
+    dec_bytes = steps * L * (2 * 3.0 * H * F * 2)   # two experts per token and layer
+    graph = None
+    if not brief:
+        # the same steps replayed from one HIP graph per step (no per-stage events inside a graph, so wall time only)
+        graph_counts = st.new_counts()
+        step = stack.CapturedStep(st, 1, graph_counts)
+        step.h_in.copy_(hs[0])
         step.replay()
-    torch.cuda.synchronize()
-    g_wall = time.perf_counter() - t0
-    graph_matches = bool(torch.equal(graph_counts, decode))
+        graph_counts.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for h in hs:
+            step.h_in.copy_(h)
+            step.replay()
+        torch.cuda.synchronize()
+        g_wall = time.perf_counter() - t0
+        graph = {"wall_ms": g_wall * 1e3, "tokens_per_s_wall": steps / g_wall, "GBps_wall": dec_bytes / g_wall / 1e9,
+                 "frac_of_hbm_peak_wall": dec_bytes / g_wall / 1e9 / PEAK_HBM_GBS,
+                 "counts_equal_eager_run": bool(torch.equal(graph_counts, decode))}
     P, D = prefill[:, :E].contiguous(), decode[:, :E].contiguous()
     sim, per = policy.daop_similarity(P, D)
     win_mean, win_pairs = policy.daop_window_variation(selections, E, 15)   # Sec. VI-B: 15-token decode windows
@@ -129,14 +147,14 @@ def run_stack(args):
     hq = torch.cat(hs[:8], dim=0)
     exact_h = st.forward(hq, st.new_counts())["h"].clone()
     precalc = []
-    for ecr in (0.25, 0.46875, 0.75, 1.0):
+    for ecr in (() if brief else (0.25, 0.46875, 0.75, 1.0)):
         c = policy.daop_memory_init(D, int(round(ecr * L * E)))
         policy.daop_plan_swaps(P, c)
         r = stack.forward_precalc(st, hq, c, first_predicted_layer=5)
         precalc.append({"expert_cache_ratio": ecr, "stale_selections": r["stale_selections"],
                         "rel_err_final_hidden": ((r["h"] - exact_h).norm() / exact_h.norm()).item()})
-    dec_bytes = steps * L * (2 * 3.0 * H * F * 2)   # two experts per token and layer
-    print(json.dumps({
+    gave_up = moe.moe_decode_status(st.workspace)
+    result = {
         "metric": "moe_stack_decode_tokens_per_s", "value": steps / (d_gpu_ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.model}_stack_{L}_layers_prefill_T{T}_then_{steps}_decode_steps", "layers": L,
@@ -146,9 +164,7 @@ def run_stack(args):
                     "tflops_moe_gpu_time": L * T * 12.0 * H * F / (p_gpu_ms * 1e-3) / 1e12},
         "decode": {"steps": steps, "moe_gpu_ms": d_gpu_ms, "wall_ms": d_wall * 1e3,
                    "tokens_per_s_moe_gpu_time": steps / (d_gpu_ms * 1e-3), "tokens_per_s_wall": steps / d_wall,
-                   "graph_replay": {"wall_ms": g_wall * 1e3, "tokens_per_s_wall": steps / g_wall,
-                                    "GBps_wall": dec_bytes / g_wall / 1e9, "frac_of_hbm_peak_wall": dec_bytes / g_wall / 1e9 / PEAK_HBM_GBS,
-                                    "counts_equal_eager_run": graph_matches},
+                   "graph_replay": graph, "rendezvous_gave_up": gave_up,
                    "GBps_moe_gpu_time": dec_bytes / (d_gpu_ms * 1e-3) / 1e9,
                    "frac_of_hbm_peak_moe_gpu_time": dec_bytes / (d_gpu_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
         "prediction_agreement": {"prefill_exact_set_mean": exact.mean().item(), "prefill_overlap_mean": overlap.mean().item(),
@@ -163,7 +179,10 @@ def run_stack(args):
                        "prefill_tokens_on_resident_experts_after": resident_after},
         "precalculation_error_vs_cache_ratio": precalc,
         "prefill_counts_first_layers": P[:2].cpu().tolist(),
-    }))
+    }
+    del st
+    torch.cuda.empty_cache()
+    return result
 
 
 def time_steps(fn, steps, warmup):
@@ -191,14 +210,148 @@ def stage_times(fn, steps):
     return moe.moe_stage_timing_end()
 
 
+def kernel_source_digest():
+    """Short hash of the kernel sources: a stored traffic figure is only quoted for the sources it was measured on."""
+    import hashlib
+
+    h = hashlib.sha256()
+    base = os.path.join(ROOT, "paper_2501_10375_amd", "csrc")
+    for name in sorted(os.listdir(base)):
+        with open(os.path.join(base, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(key):
-    """Per-launch HBM bytes of a kernel from the committed rocprofv3 --pmc summary, if there is one."""
+    """Per-launch HBM bytes of a kernel from the committed rocprofv3 --pmc summary.  Counters cannot be read from
+    inside this process, so the figure is a stored one: it is returned together with where it comes from, and only
+    if the kernel sources are still the ones it was measured on (otherwise null, with the reason)."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(key)
+            t = json.load(f)
     except (OSError, ValueError):
-        return None
+        return None, "no profiles/traffic.json"
+    if key not in t:
+        return None, "no counter run stored for this kernel and workload"
+    src = f"{t.get('_source', 'profiles/')} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, measured separately; not read in this run)"
+    if t.get("_kernel_source_digest") != kernel_source_digest():
+        return None, "stored figure is for other kernel sources: " + src
+    return t[key], src
+
+
+def prefill_leg(model, T, steps, warmup, d=None):
+    """One prefill-size moe_layer workload (counts and prediction on): timing, per-stage kernel times, both
+    roofline fractions of the layer and the roofline of its dominant kernel (the first grouped GEMM)."""
+    import torch
+    from paper_2501_10375_amd import moe, synth
+
+    cfg = WORKLOADS[model]
+    H, F, E, k = cfg["H"], cfg["F"], cfg["E"], cfg["k"]
+    dev, dtype = "cuda:0", torch.bfloat16
+    shape = moe.make_shape(H, F, E, k, dtype)
+    if d is None:
+        d = synth.moe_layer_inputs(T, H, F, E, dtype, dev, seed=0, zipf_s=cfg["zipf"], with_next=True)
+    elif d["x"].shape[0] != T:
+        d = dict(d, x=synth.normal((T, H), 0, synth.TID_X, 1.0, dtype, dev))
+    out = moe.LayerOutputs(shape, T, dtype, dev, predict=True)
+
+    def step():
+        moe.run_layer(shape, d, out)
+
+    sec = time_steps(step, steps, warmup)
+    st = stage_times(step, steps)
+    counts = out.counts.cpu().tolist()
+    A = T * k
+    active = sum(1 for c in counts if c > 0)
+    flops_layer = T * (12.0 * H * F + 2 * 2.0 * H * E)
+    # bytes: each active expert's weights once, x in, y out, the bf16 intermediate written and read
+    bytes_layer = active * 3.0 * H * F * 2 + 2.0 * T * H * 2 + 2.0 * A * F * 2
+    t_mfma, t_hbm = flops_layer / (PEAK_BF16_TFLOPS * 1e12), bytes_layer / (PEAK_HBM_GBS * 1e9)
+    flops_gemm1 = 4.0 * A * H * F
+    bytes_gemm1 = active * 2.0 * H * F * 2 + A * H * 2.0 + A * F * 2.0
+    g1_ms = st["gemm1"][0]
+    mfma_bound = flops_gemm1 / (PEAK_BF16_TFLOPS * 1e12) >= bytes_gemm1 / (PEAK_HBM_GBS * 1e9)
+    key = f"{model}_prefill_T{T}_gemm1"
+    traffic, traffic_source = read_traffic(key)
+    if mfma_bound:
+        ach = flops_gemm1 / (g1_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "grouped_gemm_bf16<gemm1+swiglu>", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
+                    "kernel_ms": g1_ms, "algorithmic_flops_per_launch": flops_gemm1}
+    else:
+        ach = bytes_gemm1 / (g1_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "grouped_gemm_bf16<gemm1+swiglu>", "achieved": ach, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                    "kernel_ms": g1_ms, "algorithmic_bytes_per_launch": bytes_gemm1,
+                    "frac_of_mfma_peak": flops_gemm1 / (g1_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    leg = {
+        "workload": f"{model}_layer_prefill_T{T}_bf16_top{k}_with_counts_and_prediction", "tokens": T,
+        "value": T / sec, "unit": "tokens/s", "ms_per_step": sec * 1e3, "steps": steps,
+        "layer_tflops": flops_layer / sec / 1e12, "layer_frac_of_mfma_peak": flops_layer / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "layer_GBps": bytes_layer / sec / 1e9, "layer_frac_of_hbm_peak": bytes_layer / sec / 1e9 / PEAK_HBM_GBS,
+        "layer_bound": "mfma" if t_mfma >= t_hbm else "hbm", "layer_frac_of_bound": max(t_mfma, t_hbm) / sec,
+        "active_experts": active, "counts": counts,
+        "stage_ms": {name: round(v[0], 5) for name, v in st.items() if v[1] > 0}, "roofline": roofline,
+    }
+    return leg, d, out
+
+
+def decode_leg(model, Td, steps, warmup, layers):
+    """Decode-size moe_layer calls (no prediction) rotating over distinct weight sets so the weights stay cold."""
+    import torch
+    from paper_2501_10375_amd import moe, synth
+
+    cfg = WORKLOADS[model]
+    H, F, E, k = cfg["H"], cfg["F"], cfg["E"], cfg["k"]
+    dev, dtype = "cuda:0", torch.bfloat16
+    shape = moe.make_shape(H, F, E, k, dtype)
+    xs = synth.normal((Td, H), 1000, synth.TID_X, 1.0, dtype, dev)
+    outs = moe.LayerOutputs(shape, Td, dtype, dev, predict=False)
+    calls = [dict(L, x=xs, wg_next=None, bias_next=None) for L in layers]
+    prepared = [moe.PreparedLayerCall(shape, c, outs, predict=False) for c in calls]  # arguments marshalled once
+    state = {"i": 0}
+
+    def dstep():
+        prepared[state["i"] % len(prepared)]()
+        state["i"] += 1
+
+    n = max(steps, 4 * len(calls))
+    dsec = time_steps(dstep, n, max(warmup, len(calls)))
+    state["i"] = 0
+    dst = stage_times(dstep, n)
+    distinct = []   # distinct experts hit, per weight set (the routing differs per set)
+    for c in calls:
+        moe.run_layer(shape, c, outs, predict=False)
+        distinct.append(int((outs.counts > 0).sum().item()))
+    gave_up = moe.moe_decode_status(outs.workspace)
+    Dm = sum(distinct) / len(distinct)
+    bytes_layer = Dm * 3.0 * H * F * 2 + 2 * Td * H * 2 + E * H * 2
+    bytes_kernel = Dm * 3.0 * H * F * 2  # the one kernel of a decode call streams all three matrices
+    g1 = dst["fused"][0]
+    traffic, traffic_source = read_traffic(f"{model}_decode_T{Td}_layer")
+    return {
+        "workload": f"{model}_layer_decode_T{Td}_bf16", "tokens": Td, "value": Td / dsec,
+        "unit": "tokens/s", "ms_per_step": dsec * 1e3, "steps": n, "weight_sets": len(calls),
+        "distinct_experts_mean": Dm, "layer_GBps": bytes_layer / dsec / 1e9,
+        "layer_frac_of_hbm_peak": bytes_layer / dsec / 1e9 / PEAK_HBM_GBS, "rendezvous_gave_up": gave_up,
+        "stage_ms": {name: round(v[0], 5) for name, v in dst.items() if v[1] > 0},
+        "roofline": {"bound": "hbm", "kernel": "decode_layer_kernel",
+                     "achieved": bytes_kernel / (g1 * 1e-3) / 1e9 if g1 > 0 else None,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": bytes_kernel / (g1 * 1e-3) / 1e9 / PEAK_HBM_GBS if g1 > 0 else None,
+                     "traffic": traffic, "traffic_source": traffic_source, "kernel_ms": g1,
+                     "algorithmic_bytes_per_launch": bytes_kernel},
+    }
+
+
+def weight_sets(model, first, n):
+    import torch
+    from paper_2501_10375_amd import synth
+
+    cfg = WORKLOADS[model]
+    return [first] + [synth.moe_layer_inputs(1, cfg["H"], cfg["F"], cfg["E"], torch.bfloat16, "cuda:0", seed=s,
+                                             zipf_s=cfg["zipf"], with_next=False) for s in range(1, max(1, n))]
 
 
 def main():
@@ -223,48 +376,23 @@ def main():
     moe.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.workload == "stack":
-        run_stack(args)
+        print(json.dumps(run_stack(args)))
         return
-    dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = WORKLOADS[args.model]
     H, F, E, k = cfg["H"], cfg["F"], cfg["E"], cfg["k"]
-    dtype = torch.bfloat16
     T = args.tokens
-    shape = moe.make_shape(H, F, E, k, dtype)
 
     # ---- headline: prefill of one sequence, with counts and next-layer prediction ----------------
-    d = synth.moe_layer_inputs(T, H, F, E, dtype, dev, seed=0, zipf_s=cfg["zipf"], with_next=True)
-    out = moe.LayerOutputs(shape, T, dtype, dev, predict=True)
-
-    def step():
-        moe.run_layer(shape, d, out)
-
-    sec = time_steps(step, args.steps, args.warmup)
-    st = stage_times(step, args.steps)
-    counts = out.counts.cpu().tolist()
-    A = T * k
-    flops_layer = T * (12.0 * H * F + 2 * 2.0 * H * E)
-    flops_gemm1 = 4.0 * A * H * F
-    g1_ms = st["gemm1"][0]
-    roofline = {
-        "bound": "mfma", "kernel": "grouped_gemm_bf16<gemm1+swiglu>",
-        "achieved": flops_gemm1 / (g1_ms * 1e-3) / 1e12 if g1_ms > 0 else None,
-        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": (flops_gemm1 / (g1_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if g1_ms > 0 else None,
-        "traffic": read_traffic(f"{args.model}_prefill_T{T}_gemm1"),
-        "kernel_ms": g1_ms, "algorithmic_flops_per_launch": flops_gemm1,
-    }
+    head, d, out = prefill_leg(args.model, T, args.steps, args.warmup)
     result = {
-        "metric": "moe_layer_tokens_per_s", "value": T / sec, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "metric": "moe_layer_tokens_per_s", "value": head["value"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.model}_layer_prefill_T{T}_bf16_top{k}_with_counts_and_prediction",
-                   "hidden": H, "ffn": F, "n_experts": E, "top_k": k, "tokens": T, "gate_bias": f"zipf({cfg['zipf']})",
-                   "counts": counts},
-        "layer_tflops": flops_layer / sec / 1e12, "layer_frac_of_mfma_peak": flops_layer / sec / 1e12 / PEAK_BF16_TFLOPS,
-        "stage_ms": {name: round(v[0], 5) for name, v in st.items() if v[1] > 0},
-        "roofline": roofline,
+        "config": {"workload": head["workload"], "hidden": H, "ffn": F, "n_experts": E, "top_k": k, "tokens": T,
+                   "gate_bias": f"zipf({cfg['zipf']})", "counts": head["counts"]},
+        "layer_tflops": head["layer_tflops"], "layer_frac_of_mfma_peak": head["layer_frac_of_mfma_peak"],
+        "stage_ms": head["stage_ms"], "roofline": head["roofline"],
     }
 
     # ---- context for the MFMA roofline: what a register-only MFMA loop reaches on this board, with
@@ -272,51 +400,22 @@ def main():
     # roofline's `peak` stays the published 2.5 PFLOP/s; these two are measured, a few ms each.
     probe = {name: moe.moe_calibrate_mfma(rnd) for name, rnd in (("constant_operands", False), ("random_operands", True))}
     result["mfma_probe"] = {"unit": "TFLOP/s", **{name: round(v["tflops"], 1) for name, v in probe.items()},
-                            "shader_clock_GHz": {name: round(v["ghz"], 3) for name, v in probe.items()},
-                            "gemm1_frac_of_random_operand_rate": roofline["achieved"] / probe["random_operands"]["tflops"]}
+                            "shader_clock_GHz": {name: round(v["ghz"], 3) for name, v in probe.items()}}
+    if head["roofline"]["bound"] == "mfma":
+        result["mfma_probe"]["gemm1_frac_of_random_operand_rate"] = head["roofline"]["achieved"] / probe["random_operands"]["tflops"]
+
+    # ---- the other prefill lengths of the same layer (shorter ones move from the MFMA bound to the HBM bound)
+    result["prefill"] = []
+    for Tp in args.prefill_tokens:
+        if Tp != T:
+            result["prefill"].append(prefill_leg(args.model, Tp, args.steps, args.warmup, d)[0])
 
     # ---- decode: a few tokens per call, weights cold (rotate over distinct weight sets) -----------
     decode = []
     if args.decode_tokens:
-        layers = [d] + [synth.moe_layer_inputs(1, H, F, E, dtype, dev, seed=s, zipf_s=cfg["zipf"], with_next=False)
-                        for s in range(1, max(1, args.decode_layers))]
+        layers = weight_sets(args.model, d, args.decode_layers)
         for Td in args.decode_tokens:
-            xs = synth.normal((Td, H), 1000, synth.TID_X, 1.0, dtype, dev)
-            outs = moe.LayerOutputs(shape, Td, dtype, dev, predict=False)
-            calls = [dict(L, x=xs, wg_next=None, bias_next=None) for L in layers]
-            prepared = [moe.PreparedLayerCall(shape, c, outs, predict=False) for c in calls]  # arguments marshalled once
-            state = {"i": 0}
-
-            def dstep():
-                prepared[state["i"] % len(prepared)]()
-                state["i"] += 1
-
-            n = max(args.steps, 4 * len(calls))
-            dsec = time_steps(dstep, n, max(args.warmup, len(calls)))
-            state["i"] = 0
-            dst = stage_times(dstep, n)
-            # distinct experts hit, per weight set (the routing differs per set)
-            distinct = []
-            for c in calls:
-                moe.run_layer(shape, c, outs, predict=False)
-                distinct.append(int((outs.counts > 0).sum().item()))
-            Dm = sum(distinct) / len(distinct)
-            bytes_layer = Dm * 3.0 * H * F * 2 + 2 * Td * H * 2 + E * H * 2
-            bytes_kernel = Dm * 3.0 * H * F * 2  # the one kernel of a decode call streams all three matrices
-            g1 = dst["fused"][0]
-            decode.append({
-                "workload": f"{args.model}_layer_decode_T{Td}_bf16", "tokens": Td, "value": Td / dsec,
-                "unit": "tokens/s", "ms_per_step": dsec * 1e3, "steps": n, "weight_sets": len(calls),
-                "distinct_experts_mean": Dm, "layer_GBps": bytes_layer / dsec / 1e9,
-                "layer_frac_of_hbm_peak": bytes_layer / dsec / 1e9 / PEAK_HBM_GBS,
-                "stage_ms": {name: round(v[0], 5) for name, v in dst.items() if v[1] > 0},
-                "roofline": {"bound": "hbm", "kernel": "decode_layer_kernel",
-                             "achieved": bytes_kernel / (g1 * 1e-3) / 1e9 if g1 > 0 else None,
-                             "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                             "frac": bytes_kernel / (g1 * 1e-3) / 1e9 / PEAK_HBM_GBS if g1 > 0 else None,
-                             "traffic": read_traffic(f"{args.model}_decode_T{Td}_layer"), "kernel_ms": g1,
-                             "algorithmic_bytes_per_launch": bytes_kernel},
-            })
+            decode.append(decode_leg(args.model, Td, args.steps, args.warmup, layers))
         del layers
     result["decode"] = decode
     # ---- context for the HBM roofline: a plain read stream over one weight tensor of the layer (0.94 GB for the
@@ -353,6 +452,30 @@ def main():
             "sample": f"routing + prediction on all {T} tokens ({t_route:.2f} s), expert FFN + combine on {n} evenly "
                       f"spaced tokens ({t_ffn:.2f} s); fp64 C oracle, OpenMP over tokens",
         }
+        del h, ref
+    del d, out
+    torch.cuda.empty_cache()
+
+    # ---- the second model shape of the paper (Table III): Phi-3.5-MoE-shaped, 16 experts, stronger skew
+    if args.other_model and args.other_model != args.model:
+        om = args.other_model
+        leg, od, oout = prefill_leg(om, args.other_prefill, args.steps, args.warmup)
+        other = {"model": om, "prefill": [leg], "decode": []}
+        layers = weight_sets(om, od, args.decode_layers)
+        for Td in args.other_decode_tokens:
+            other["decode"].append(decode_leg(om, Td, args.steps, args.warmup, layers))
+        del layers, od, oout
+        torch.cuda.empty_cache()
+        result["other_model"] = other
+
+    # ---- the resident stack of layers (one prefill, then single-token decode steps)
+    if args.with_stack:
+        free, _ = torch.cuda.mem_get_info()
+        need = args.stack_layers * E * 3 * H * F * 2 + (6 << 30)
+        if free >= need:
+            result["stack"] = run_stack(args, brief=True)
+        else:
+            result["stack"] = {"skipped": f"needs {need >> 30} GiB of free device memory, {free >> 30} GiB available"}
     print(json.dumps(result))
 
 

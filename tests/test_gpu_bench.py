@@ -30,7 +30,8 @@ def _run_bench(argv):
 
 
 def test_layer_line_has_the_contract_fields():
-    r = _run_bench(["--tokens", "2304", "--steps", "2", "--warmup", "1", "--decode-tokens", "1", "--cpu-sample", "4"])
+    r = _run_bench(["--tokens", "2304", "--steps", "2", "--warmup", "1", "--decode-tokens", "1", "--cpu-sample", "4",
+                    "--prefill-tokens", "512", "--other-model", "", "--no-stack"])
     for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
                 "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
         assert key in r, key
@@ -41,7 +42,11 @@ def test_layer_line_has_the_contract_fields():
     roof = r["roofline"]
     assert roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s" and roof["peak"] == 2500.0
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9 and 0.0 < roof["frac"] < 1.0
-    assert "traffic" in roof
+    assert "traffic" in roof and roof["traffic_source"]
+    short = r["prefill"][0]   # 512 tokens: below the ridge, priced against the HBM bound, both fractions reported
+    assert short["tokens"] == 512 and short["layer_bound"] == "hbm" and 0.0 < short["layer_frac_of_hbm_peak"] < 1.0
+    assert 0.0 < short["layer_frac_of_mfma_peak"] < 1.0 and short["roofline"]["bound"] == "hbm"
+    assert r["decode"][0]["rendezvous_gave_up"] is False
     cpu = r["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["unit"] == "tokens/s" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     dec = r["decode"][0]["roofline"]
