@@ -25,7 +25,6 @@ namespace {
 //       empty slot fragments skipped.  Two K steps in flight hide the load latency that bounds a tile
 //       with little arithmetic, and half-height tiles pad cold experts less (40 to 1024 tokens:
 //       1-17 % faster, Phi-shaped layer up to 16 %).
-// MOE_GEMM_BK / MOE_GEMM_STAGES (/ MOE_GEMM_BT) force one shape for every call (tuning).
 constexpr int kRaggedRowsPerExpert = 512;  // mean routed rows per expert below which a call counts as ragged
 constexpr int kWT = 2, kWW = 4;  // wavefront grid: slot groups x weight-row groups
 
@@ -56,15 +55,15 @@ __global__ __launch_bounds__(256) void combine_bf16(const float* __restrict__ ou
 }
 
 // gemm1 (+ SwiGLU) and gemm2 with one pipeline shape.
-template <int BK, int STAGES, bool SKIP, int BT = gg::kBT>
+template <int BK, int STAGES, bool SKIP, int BT = gg::kBT, bool W3 = false>
 hipError_t launch_gemms(const moe_shape_t& s, const uint16_t* x, const uint16_t* act_in, const uint16_t* w1,
                         const uint16_t* w3, const uint16_t* w2, const int32_t* offs, const int32_t* row_of_slot,
                         void* act, float* out, int32_t* sync, float* partial, const StaleInput& alt, hipStream_t stream) {
-    using G1 = gg::Gemm<2, BK, STAGES, kWT, kWW, SKIP, BT>;
-    using G2 = gg::Gemm<1, BK, STAGES, kWT, kWW, SKIP, BT>;
-    auto k1 = gg::grouped_gemm_kernel<2, BK, STAGES, kWT, kWW, SKIP, BT>;
-    auto k2 = gg::grouped_gemm_kernel<1, BK, STAGES, kWT, kWW, SKIP, BT>;
-    auto k1_alt = gg::grouped_gemm1_alt_kernel<BK, STAGES, kWT, kWW, SKIP, BT>;
+    using G1 = gg::Gemm<2, BK, STAGES, kWT, kWW, SKIP, BT, false, W3>;
+    using G2 = gg::Gemm<1, BK, STAGES, kWT, kWW, SKIP, BT, false, W3>;
+    auto k1 = gg::grouped_gemm_kernel<2, BK, STAGES, kWT, kWW, SKIP, BT, W3>;
+    auto k2 = gg::grouped_gemm_kernel<1, BK, STAGES, kWT, kWW, SKIP, BT, W3>;
+    auto k1_alt = gg::grouped_gemm1_alt_kernel<BK, STAGES, kWT, kWW, SKIP, BT, W3>;
     static bool configured = false;  // raising the dynamic LDS limit is idempotent; a race only repeats it
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
@@ -107,16 +106,8 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
                    *p2 = static_cast<const uint16_t*>(w2);
     hipError_t e;
     const bool ragged = (long)tokens * s.top_k < (long)s.n_experts * kRaggedRowsPerExpert;
-#if defined(MOE_GEMM_BK) && defined(MOE_GEMM_STAGES)
-#ifndef MOE_GEMM_BT
-#define MOE_GEMM_BT 256
-#endif
-    e = ragged ? launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, true, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream)
-               : launch_gemms<MOE_GEMM_BK, MOE_GEMM_STAGES, false, MOE_GEMM_BT>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream);
-#else
     e = ragged ? launch_gemms<64, 3, true, 128>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream)
-               : launch_gemms<64, 2, false, 256>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream);
-#endif
+               : launch_gemms<64, 2, false, 256, true>(s, xs, a16, p1, p3, p2, offs, row_of_slot, act, out, sync, partial, alt, stream);
     if (e != hipSuccess) return e;
     combine_bf16<<<tokens, 256, 0, stream>>>(out, topk_w, slot_of, s.top_k, s.hidden, static_cast<uint16_t*>(y));
     stage_mark(stream, kStageCombine);
@@ -124,3 +115,4 @@ hipError_t launch_ffn_bf16(const moe_shape_t& s, int tokens, const void* x, cons
 }
 
 }  // namespace moe
+

@@ -75,22 +75,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // Pipeline depths (64-element K steps of loads in flight per wavefront) of the two GEMM phases.
-#ifndef MOE_DEC_P1
-#define MOE_DEC_P1 1
-#endif
-#ifndef MOE_DEC_P2
-#define MOE_DEC_P2 2
-#endif
+constexpr int kP1 = 1, kP2 = 2;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-// Optional timestamps per workgroup for tuning (compiled out unless MOE_DEC_TRACE is defined).
-#ifdef MOE_DEC_TRACE
-__device__ unsigned long long g_dec_trace[512][8];
-#define DEC_TRACE(slot) do { if (threadIdx.x == 0) g_dec_trace[blockIdx.x][slot] = wall_clock64(); } while (0)
-#else
-#define DEC_TRACE(slot) do { } while (0)
-#endif
 // How the 8 wavefronts of a workgroup split K: interleaved 64-element steps (wavefront w takes steps
 // w, w + 8, ...), so that at any moment the workgroup reads one contiguous 1 KB piece of each weight row.
 struct KSplit {
@@ -664,7 +652,6 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
         if (a_open) __hip_atomic_store(&p.flags[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&p.flags[kFlagStride + blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    DEC_TRACE(3);
     if (total_q == 0) return;
 
     u32x4 lo[P], hi[P], aa[P][NC], ab[P][NC];
@@ -713,7 +700,6 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
             if (b_open && ad >= d_a) {  // the next operand belongs to group B
                 await_flags(p.flags + kFlagStride, n_wgs, epoch, p.spin_limit, p.flags + kStatusIndex, &sm.failed);
                 b_open = false;
-                DEC_TRACE(6);
             }
             enter_a();
         }
@@ -723,7 +709,6 @@ __device__ inline void gemm2_phase(const DecodeArgs& p, Smem<NC>& sm, uint32_t e
 
     // ---- group A of the intermediate is needed now
     await_flags(p.flags, n_wgs, epoch, p.spin_limit, p.flags + kStatusIndex, &sm.failed);
-    DEC_TRACE(4);
 #pragma unroll
     for (int i = 0; i < P; ++i) issue_a(i);
 
@@ -801,7 +786,6 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
     // (Requested here, used after the routing, so its latency costs nothing.)
     const uint32_t last_count = __hip_atomic_load(&p.flags[kEpochIndex], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("" ::: "memory");
-    DEC_TRACE(0);
     for (int i = tid; i < 16 * NC * 16; i += kThreads) sm.yacc[i >> 4][i & 15] = 0.f;
     if (tid == 0) sm.failed = 0;
     if (ROUTE) {
@@ -836,9 +820,7 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
         }
     }
     __syncthreads();
-    DEC_TRACE(1);
     build_groups<NC>(sm.g, sm.idx, A, p.E);
-    DEC_TRACE(2);
     const uint32_t count = (uint32_t)__builtin_amdgcn_readfirstlane((int)last_count) + 1u;
     const uint32_t epoch = count ^ 0x9E3779B9u;
     bool a_open = true;  // flag A not raised yet
@@ -856,7 +838,6 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
                                   reinterpret_cast<float*>(&sm.red[0][0][0][0][0]));
         if (tid < A) p.pred_out[tid] = sm.route.idx[tid];
     }
-    DEC_TRACE(5);
 }
 
 }  // namespace
@@ -898,14 +879,14 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     const int max_tiles1 = min(s.n_experts, tokens * s.top_k) * (s.ffn / 16);
     const int grid = min(min(compute_units(), kFlagStride), max(max_tiles1, s.hidden / 16));
     if (route != nullptr) {
-        decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, true, 1><<<grid, kThreads, 0, stream>>>(p);
+        decode_layer_kernel<kP1, kP2, true, 1><<<grid, kThreads, 0, stream>>>(p);
     } else if (alt.stale != nullptr) {
-        if (tokens <= 16) decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 1, true><<<grid, kThreads, 0, stream>>>(p);
-        else decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 2, true><<<grid, kThreads, 0, stream>>>(p);
+        if (tokens <= 16) decode_layer_kernel<kP1, kP2, false, 1, true><<<grid, kThreads, 0, stream>>>(p);
+        else decode_layer_kernel<kP1, kP2, false, 2, true><<<grid, kThreads, 0, stream>>>(p);
     } else if (tokens <= 16) {
-        decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 1><<<grid, kThreads, 0, stream>>>(p);
+        decode_layer_kernel<kP1, kP2, false, 1><<<grid, kThreads, 0, stream>>>(p);
     } else {
-        decode_layer_kernel<MOE_DEC_P1, MOE_DEC_P2, false, 2><<<grid, kThreads, 0, stream>>>(p);
+        decode_layer_kernel<kP1, kP2, false, 2><<<grid, kThreads, 0, stream>>>(p);
     }
     stage_mark(stream, kStageFused);
     return hipGetLastError();

@@ -60,10 +60,7 @@ constexpr size_t kScratchBytes = (size_t)kXcds * kMaxWgsPerXcd * kPartialFloats 
 // tile, slot tile within the group.  32 consecutive tiles (what the 32 CUs of one XCD work on at
 // one time) are then about 8 slot tiles x 4 feature tiles of one expert: 12 distinct operand tiles
 // feed 32 workgroups through the XCD's L2.
-#ifndef MOE_GEMM_GROUP
-#define MOE_GEMM_GROUP 8
-#endif
-constexpr int kGroup = MOE_GEMM_GROUP;
+constexpr int kGroup = 8;
 
 __device__ inline int count_tiles(const int32_t* __restrict__ offs, int E, int n_ftiles, int bt) {
     int total = 0;
@@ -158,8 +155,19 @@ struct Swz<32> {  // 64-byte rows, 4 pieces; four rows span the 64 banks
 // scalar branch, which costs a little when nearly all tiles are full; the launcher decides.
 // ALT (gemm1 only): a slot's row comes from `tok_alt` instead of `tok_base` when alt_mask[assignment]
 // is set: expert execution with some selections pre-calculated on an earlier hidden state.
-template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT, bool ALT = false>
+//
+// W3: three weight stages and two slot stages (160 KB of LDS) instead of STAGES stages of both.  With two
+// stages of both operands a K step's loads can only be requested after the barrier that starts the K
+// step before, all at once: the 64 load instructions of a workgroup then queue in the CU's address
+// path for about a thousand cycles, and the MFMAs interleaved with them are held back as long (a
+// wavefront issues in order).  Weight lines are the ones that come from memory, slot lines mostly
+// from the L2 or the memory-side cache; so the weights get the third stage: they are requested two K
+// steps ahead and their load instructions are spread evenly over a K step, and only the slot loads
+// (half the instructions) remain tied to the barrier.  Stage offsets rotate at run time (scalar
+// registers), so the loop body is one K step and needs few address registers.
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT, bool ALT = false, bool W3 = false>
 struct Gemm {
+    static_assert(!W3 || (STAGES == 2 && BK == 64 && BT == kBT && !SKIP), "the three-weight-stage flavour is built for full tiles");
     static_assert(!ALT || NMAT == 2, "only the first GEMM gathers rows of x");
     static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
     static constexpr int kThreads = kWaves * 64;
@@ -173,7 +181,7 @@ struct Gemm {
     static constexpr int kTokTileBytes = BT * kRowBytes;       // the slot tile of one stage
     static constexpr int kTileBytes = 256 * kRowBytes;         // the weight tile of one stage
     static constexpr int kStageBytes = kTokTileBytes + kTileBytes;  // slots, then weights
-    static constexpr int kLdsBytes = STAGES * kStageBytes;
+    static constexpr int kLdsBytes = W3 ? 3 * kTileBytes + 2 * kTokTileBytes : STAGES * kStageBytes;
     static constexpr int kRowsPerLoad = 1024 / kRowBytes;      // rows covered by one wavefront-wide 1 KB load
     static_assert(kTokStageRows % kRowsPerLoad == 0, "whole loads per wavefront");
     static constexpr int kLoadsTok = kTokStageRows / kRowsPerLoad;  // slot loads per thread per stage
@@ -286,26 +294,6 @@ struct Gemm {
         const uint32_t stage_off_tok = (uint32_t)(wave * kTokStageRows * kRowBytes);
         const uint32_t stage_off_w = (uint32_t)(kTokTileBytes + wave * kStageRows * kRowBytes);
 
-        // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
-        // computed, and within a k16 step one at a time between MFMAs (see step() below).
-        // With only two stages the next K step is requested at once, in the first k16 step, so that it
-        // has the whole K step to arrive; with a deeper ring the requests are spread over all k16 steps.
-        constexpr int kM = kWF * kTF, kR = kWF + kTF;
-        constexpr int kDmaParts = STAGES == 2 ? (kLoads <= kM ? 1 : 2) : (kLoads % kKSteps == 0 ? kKSteps : 2);
-        static_assert(kLoads % kDmaParts == 0, "loads per stage must split evenly over the k16 steps that issue them");
-        constexpr int kLoadsPerPart = kLoads / kDmaParts;
-        // SKIP: a wavefront whose 32 slot rows all lie past the tile's last slot stages no slot rows (the
-        // fragments they would feed are skipped as well): a ragged tile then moves its weights plus only
-        // its own slot rows through the load path, which is what bounds tiles of cold experts.
-        static_assert(32 % kTokStageRows == 0, "a wavefront stages rows of one 32-slot fragment");
-        const bool stage_tok = !SKIP || (wave * kTokStageRows) / 32 * 32 < rows;  // its fragment has valid slots
-        auto dma_one = [&](int stage, int kt, int l) {
-            if (SKIP && l < kLoadsTok && !stage_tok) return;
-            const uint32_t base = lds0 + (uint32_t)stage * kStageBytes;
-            dma16(gp[l] + (size_t)kt * kRowBytes,
-                  base + (l < kLoadsTok ? stage_off_tok + l * 1024 : stage_off_w + (l - kLoadsTok) * 1024));
-        };
-
         f32x16 acc[kWF][kTF];  // [weight frag][slot frag]
 #pragma unroll
         for (int j = 0; j < kWF; ++j)
@@ -330,75 +318,184 @@ struct Gemm {
         for (int j = 0; j < kWF; ++j)
             wrow[j] = (j / kFragsPerMat) * 128 * (NMAT - 1) + wq * kFeatPerWave + (j % kFragsPerMat) * 32 + frow;
 
-        // Operand fragments are double-buffered in registers (buffer = k16 step & 1).  One pipeline
-        // step issues the MFMAs of one k16 step and, BETWEEN them one for one, the LDS reads of the
-        // next step's fragments (into the other buffer) and this wavefront's share of the global->LDS
-        // loads of a later K step.  Interleaving matters: a burst of ds_reads from all wavefronts right
-        // after a barrier fills the LDS command queue and blocks the issuing wavefronts, MFMAs
-        // included; one read per MFMA keeps the matrix pipe fed while the queue drains.  The MFMAs of a
-        // K step's LAST k16 step run after the next K step's barrier, paired with its first reads, so
-        // the matrix pipe also has work while the wavefronts re-synchronise.
-        static_assert(kKSteps % 2 == 0, "fragment buffers alternate per k16 step");
-        static_assert(kLoadsPerPart <= kM, "a step has one slot per MFMA for its loads");
-        bf16x8 tf[2][kTF], wf[2][kWF];
-        auto read_one = [&](int stage, int ks, int buf, int idx) {
-            const unsigned char* st = lds + stage * kStageBytes;
-            if (idx < kWF)
-                wf[buf][idx] = *reinterpret_cast<const bf16x8*>(
-                    st + kTokTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
-            else if (!SKIP || idx - kWF < n_tf)
-                tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
-                    st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
-        };
-        // mfma: issue the MFMAs of buffer mbuf.  read: fetch fragments (rstage, rks) into buffer rbuf.
-        // dma: issue part dpart of K step dkt's loads into stage dstage.
-        auto step = [&](auto mfma, int mbuf, auto read, int rstage, int rks, int rbuf, bool dma, int dstage, int dkt,
-                        int dpart) {
+        if constexpr (W3) {
+            // A fragment read of row r, k16 step ks from a stage at byte offset `off` is at
+            //   r * 128 + ((ks * 2 + fhalf) ^ ((r >> 1) & 7)) * 16 + off  =  base(r) ^ (ks << 5) ^ off,
+            // base(r) = r * 128 + ((((r >> 1) & 7) ^ fhalf) << 4): the three terms occupy different bits
+            // (pieces of a row: bits 4-6; rows: bits 7-14; stage offsets: multiples of 32 KB).
+            // Weights ("deep" operand): three stages at 0, 32 KB, 64 KB; slots ("shallow"): two stages at 96 KB, 128 KB.
+            constexpr uint32_t kShallowBase = 3 * 32768;
+            static_assert(kTileBytes == 32768 && kTokTileBytes == 32768 && kRowBytes == 128, "address arithmetic above");
+            typedef __attribute__((address_space(3))) const unsigned char* lds_ptr;
+            const lds_ptr lds3 = (lds_ptr)lds;
+            uint32_t base_w[kWF], base_t[kTF];
 #pragma unroll
-            for (int m = 0; m < kM; ++m) {
-                if (decltype(mfma)::value) {
-                    const int i = m / kWF, j = m % kWF;
-                    if (!SKIP || i < n_tf)
+            for (int j = 0; j < kWF; ++j) base_w[j] = (uint32_t)(wrow[j] * kRowBytes + ((((wrow[j] >> 1) & 7) ^ fhalf) << 4));
+#pragma unroll
+            for (int i = 0; i < kTF; ++i) base_t[i] = (uint32_t)(trow[i] * kRowBytes + ((((trow[i] >> 1) & 7) ^ fhalf) << 4));
+            constexpr int kM = kWF * kTF, kR = kWF + kTF;
+            static_assert(kLoadsTok == 4 && kLoadsPerOperand == 4 && kM == 8, "issue slots below");
+            bf16x8 tf[2][kTF], wf[2][kWF];
+            const uint32_t wave_off = (uint32_t)(wave * 32 * kRowBytes);   // both operands: 32 rows per wavefront
+            auto dma_deep = [&](int stage, int kt, int q) {
+                dma16(gp[kLoadsTok + q] + (size_t)kt * kRowBytes, lds0 + wave_off + (uint32_t)stage * 32768 + q * 1024);
+            };
+            auto dma_shallow = [&](int stage, int kt, int q) {
+                dma16(gp[q] + (size_t)kt * kRowBytes,
+                      lds0 + kShallowBase + wave_off + (uint32_t)stage * 32768 + q * 1024);
+            };
+            // One k16 block: the MFMAs of fragment buffer mbuf, between them the reads of k16 step rks of
+            // the current stages into buffer rbuf, and loads at the MFMA slots the schedule names.
+            auto block = [&](auto mfma, int mbuf, auto read, int rks, int rbuf, uint32_t w_off, uint32_t t_off, auto shallow,
+                             bool dma, int dstage, int dkt, int q0, int n_loads) {
+#pragma unroll
+                for (int m = 0; m < kM; ++m) {
+                    if (decltype(mfma)::value) {
+                        const int i = m / kWF, j = m % kWF;
                         acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
+                    }
+                    if (decltype(read)::value && m < kR) {
+                        const uint32_t k_bits = (uint32_t)(rks << 5);
+                        if (m < kWF)
+                            wf[rbuf][m] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
+                                lds3 + (base_w[m] ^ (k_bits ^ w_off)));
+                        else
+                            tf[rbuf][m - kWF] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
+                                lds3 + (base_t[m - kWF] ^ (k_bits ^ t_off)));
+                    }
+                    // n_loads == 2: slots 2 and 6; n_loads == 4: slots 0, 2, 4, 6
+                    const bool here = n_loads == 4 ? (m % 2 == 0) : (m == 2 || m == 6);
+                    if (dma && here) {
+                        const int q = q0 + (n_loads == 4 ? m / 2 : (m == 6 ? 1 : 0));
+                        if (decltype(shallow)::value) dma_shallow(dstage, dkt, q);
+                        else dma_deep(dstage, dkt, q);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (decltype(read)::value && m < kR) read_one(rstage, rks, rbuf, m);
-                if (m >= kM - kLoadsPerPart && dma && dpart < kDmaParts)
-                    dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
-                __builtin_amdgcn_sched_barrier(0);
+            };
+            using Yes = std::true_type;
+            using No = std::false_type;
+            // prologue: deep operand of K steps 0 and 1 and shallow operand of K step 0, in the order the waits below assume
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dma_deep(0, 0, q);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dma_shallow(0, 0, q);
+            if (KT > 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) dma_deep(1, 1, q);
             }
-        };
-        using Yes = std::true_type;
-        using No = std::false_type;
+            int ds = 0, ss = 0;  // deep stage (kt % 3) and shallow stage (kt % 2) of the K step being computed
+            for (int kt = 0; kt < KT; ++kt) {
+                // Outstanding, oldest first: deep operand of K step kt, shallow operand of K step kt, deep operand of
+                // K step kt + 1 (requested during K step kt - 1 after that K step's shallow loads); the last may stay in flight.
+                if (kt + 1 < KT) wait_vmcnt<4>();
+                else wait_vmcnt<0>();
+                lds_barrier();
+                const uint32_t d_off = (uint32_t)ds * 32768, s_off = kShallowBase + (uint32_t)ss * 32768;
+                const uint32_t w_off = d_off, t_off = s_off;
+                const bool more_s = kt + 1 < KT, more_d = kt + 2 < KT;
+                const int ds2 = ds == 0 ? 2 : ds - 1;  // stage of K step kt + 2 = the one K step kt - 1 used
+                // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
+                if (kt > 0) block(Yes{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0, 2);
+                else block(No{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0, 2);
+                block(Yes{}, 0, Yes{}, 1, 1, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 2, 2);
+                block(Yes{}, 1, Yes{}, 2, 0, w_off, t_off, No{}, more_d, ds2, kt + 2, 0, 2);
+                block(Yes{}, 0, Yes{}, 3, 1, w_off, t_off, No{}, more_d, ds2, kt + 2, 2, 2);
+                ds = ds == 2 ? 0 : ds + 1;
+                ss ^= 1;
+            }
+            block(Yes{}, 1, No{}, 0, 0, 0u, 0u, No{}, false, 0, 0, 0, 2);
+        } else {
+            // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
+            // computed, and within a k16 step one at a time between MFMAs (see step() below).
+            // With only two stages the next K step is requested at once, in the first k16 step, so that it
+            // has the whole K step to arrive; with a deeper ring the requests are spread over all k16 steps.
+            constexpr int kM = kWF * kTF, kR = kWF + kTF;
+            constexpr int kDmaParts = STAGES == 2 ? (kLoads <= kM ? 1 : 2) : (kLoads % kKSteps == 0 ? kKSteps : 2);
+            static_assert(kLoads % kDmaParts == 0, "loads per stage must split evenly over the k16 steps that issue them");
+            constexpr int kLoadsPerPart = kLoads / kDmaParts;
+            // SKIP: a wavefront whose 32 slot rows all lie past the tile's last slot stages no slot rows (the
+            // fragments they would feed are skipped as well): a ragged tile then moves its weights plus only
+            // its own slot rows through the load path, which is what bounds tiles of cold experts.
+            static_assert(32 % kTokStageRows == 0, "a wavefront stages rows of one 32-slot fragment");
+            const bool stage_tok = !SKIP || (wave * kTokStageRows) / 32 * 32 < rows;  // its fragment has valid slots
+            auto dma_one = [&](int stage, int kt, int l) {
+                if (SKIP && l < kLoadsTok && !stage_tok) return;
+                const uint32_t base = lds0 + (uint32_t)stage * kStageBytes;
+                dma16(gp[l] + (size_t)kt * kRowBytes,
+                      base + (l < kLoadsTok ? stage_off_tok + l * 1024 : stage_off_w + (l - kLoadsTok) * 1024));
+            };
 
-        // prologue: STAGES - 1 K steps in flight
-#pragma unroll
-        for (int s = 0; s < STAGES - 1; ++s)
-            if (s < KT) {
-#pragma unroll
-                for (int l = 0; l < kLoads; ++l) dma_one(s, s, l);
-            }
-        for (int kt0 = 0; kt0 < KT; kt0 += STAGES) {
-#pragma unroll
-            for (int s = 0; s < STAGES; ++s) {
-                const int kt = kt0 + s;
-                if (kt < KT) {
-                    // K step kt must have landed; up to STAGES - 2 younger ones may stay in flight
-                    if (kt + STAGES - 2 >= KT) wait_vmcnt<0>();
-                    else if (stage_tok) wait_vmcnt<(STAGES - 2) * kLoads>();
-                    else wait_vmcnt<(STAGES - 2) * kLoadsPerOperand>();  // this wavefront issues weight loads only
-                    lds_barrier();
-                    const bool more = kt + STAGES - 1 < KT;
-                    const int ns = (s + STAGES - 1) % STAGES;
-                    // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
-                    if (kt > 0) step(Yes{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
-                    else step(No{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
-#pragma unroll
-                    for (int ks = 0; ks + 1 < kKSteps; ++ks)
-                        step(Yes{}, ks & 1, Yes{}, s, ks + 1, (ks + 1) & 1, more, ns, kt + STAGES - 1, ks + 1);
+            // Operand fragments are double-buffered in registers (buffer = k16 step & 1).  One pipeline
+            // step issues the MFMAs of one k16 step and, BETWEEN them one for one, the LDS reads of the
+            // next step's fragments (into the other buffer) and this wavefront's share of the global->LDS
+            // loads of a later K step.  Interleaving matters: a burst of ds_reads from all wavefronts right
+            // after a barrier fills the LDS command queue and blocks the issuing wavefronts, MFMAs
+            // included; one read per MFMA keeps the matrix pipe fed while the queue drains.  The MFMAs of a
+            // K step's LAST k16 step run after the next K step's barrier, paired with its first reads, so
+            // the matrix pipe also has work while the wavefronts re-synchronise.
+            static_assert(kKSteps % 2 == 0, "fragment buffers alternate per k16 step");
+            static_assert(kLoadsPerPart <= kM, "a step has one slot per MFMA for its loads");
+            bf16x8 tf[2][kTF], wf[2][kWF];
+            auto read_one = [&](int stage, int ks, int buf, int idx) {
+                const unsigned char* st = lds + stage * kStageBytes;
+                if (idx < kWF)
+                    wf[buf][idx] = *reinterpret_cast<const bf16x8*>(
+                        st + kTokTileBytes + wrow[idx] * kRowBytes + (Swz<BK>::piece(wrow[idx], ks * 2 + fhalf) << 4));
+                else if (!SKIP || idx - kWF < n_tf)
+                    tf[buf][idx - kWF] = *reinterpret_cast<const bf16x8*>(
+                        st + trow[idx - kWF] * kRowBytes + (Swz<BK>::piece(trow[idx - kWF], ks * 2 + fhalf) << 4));
+            };
+            // mfma: issue the MFMAs of buffer mbuf.  read: fetch fragments (rstage, rks) into buffer rbuf.
+            // dma: issue part dpart of K step dkt's loads into stage dstage.
+            auto step = [&](auto mfma, int mbuf, auto read, int rstage, int rks, int rbuf, bool dma, int dstage, int dkt,
+                            int dpart) {
+    #pragma unroll
+                for (int m = 0; m < kM; ++m) {
+                    if (decltype(mfma)::value) {
+                        const int i = m / kWF, j = m % kWF;
+                        if (!SKIP || i < n_tf)
+                            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
+                    }
+                    if (decltype(read)::value && m < kR) read_one(rstage, rks, rbuf, m);
+                    if (m >= kM - kLoadsPerPart && dma && dpart < kDmaParts)
+                        dma_one(dstage, dkt, dpart * kLoadsPerPart + m - (kM - kLoadsPerPart));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            using Yes = std::true_type;
+            using No = std::false_type;
+
+            // prologue: STAGES - 1 K steps in flight
+    #pragma unroll
+            for (int s = 0; s < STAGES - 1; ++s)
+                if (s < KT) {
+    #pragma unroll
+                    for (int l = 0; l < kLoads; ++l) dma_one(s, s, l);
+                }
+            for (int kt0 = 0; kt0 < KT; kt0 += STAGES) {
+    #pragma unroll
+                for (int s = 0; s < STAGES; ++s) {
+                    const int kt = kt0 + s;
+                    if (kt < KT) {
+                        // K step kt must have landed; up to STAGES - 2 younger ones may stay in flight
+                        if (kt + STAGES - 2 >= KT) wait_vmcnt<0>();
+                        else if (stage_tok) wait_vmcnt<(STAGES - 2) * kLoads>();
+                        else wait_vmcnt<(STAGES - 2) * kLoadsPerOperand>();  // this wavefront issues weight loads only
+                        lds_barrier();
+                        const bool more = kt + STAGES - 1 < KT;
+                        const int ns = (s + STAGES - 1) % STAGES;
+                        // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
+                        if (kt > 0) step(Yes{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
+                        else step(No{}, 1, Yes{}, s, 0, 0, more, ns, kt + STAGES - 1, 0);
+    #pragma unroll
+                        for (int ks = 0; ks + 1 < kKSteps; ++ks)
+                            step(Yes{}, ks & 1, Yes{}, s, ks + 1, (ks + 1) & 1, more, ns, kt + STAGES - 1, ks + 1);
+                    }
                 }
             }
+            step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, kDmaParts);
         }
-        step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, kDmaParts);
 
         // ---- split tiles: publish this piece; the last piece to arrive sums them all in part order.
         if (parts > 1) {
@@ -522,7 +619,7 @@ struct Gemm {
     }
 };
 
-template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT>
+template <int NMAT, int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT, bool W3 = false>
 __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uint16_t* __restrict__ tok_base,
                                                                     const uint16_t* __restrict__ wa,
                                                                     const uint16_t* __restrict__ wb,
@@ -532,19 +629,19 @@ __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm_kernel(const uin
                                                                     int32_t* __restrict__ sync,
                                                                     float* __restrict__ scratch) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
-    Gemm<NMAT, BK, STAGES, WT, WW, SKIP, BT>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync, scratch,
-                                               lds_dyn);
+    Gemm<NMAT, BK, STAGES, WT, WW, SKIP, BT, false, W3>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst,
+                                                                    sync, scratch, lds_dyn);
 }
 
 // gemm1 with per-selection input rows (see Gemm's ALT).
-template <int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT>
+template <int BK, int STAGES, int WT, int WW, bool SKIP, int BT = kBT, bool W3 = false>
 __global__ __launch_bounds__(WT * WW * 64, 1) void grouped_gemm1_alt_kernel(
     const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ tok_alt, const uint8_t* __restrict__ alt_mask,
     const uint16_t* __restrict__ wa, const uint16_t* __restrict__ wb, const int32_t* __restrict__ offs,
     const int32_t* __restrict__ row_of_slot, int E, int topk, int N, int K, void* __restrict__ dst,
     int32_t* __restrict__ sync, float* __restrict__ scratch) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds_dyn[];
-    Gemm<2, BK, STAGES, WT, WW, SKIP, BT, true>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync,
+    Gemm<2, BK, STAGES, WT, WW, SKIP, BT, true, W3>::persistent(tok_base, wa, wb, offs, row_of_slot, E, topk, N, K, dst, sync,
                                                             scratch, lds_dyn, tok_alt, alt_mask);
 }
 
