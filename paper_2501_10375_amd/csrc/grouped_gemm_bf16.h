@@ -51,7 +51,8 @@ constexpr int kMaxSplit = 8;       // K parts of a tile in the last round
 //   [8, 8 + 8 * 32)             arrival counter of each split tile (XCD-major)
 constexpr int kSyncInts = kXcds + kXcds * kMaxWgsPerXcd;
 // fp32 scratch for split tiles: one 256 x 256 partial accumulator tile per workgroup.
-constexpr size_t kPartialFloats = (size_t)kBT * kBW;
+constexpr int kMaxBT = 256;  // tallest slot tile any flavour uses
+constexpr size_t kPartialFloats = (size_t)kMaxBT * kBW;
 constexpr size_t kScratchBytes = (size_t)kXcds * kMaxWgsPerXcd * kPartialFloats * sizeof(float);
 
 // Tile list.  The number of real tiles depends on the routing (sum over experts of
@@ -171,7 +172,7 @@ struct Gemm {
     static_assert(!ALT || NMAT == 2, "only the first GEMM gathers rows of x");
     static constexpr int kWaves = WT * WW;                     // WT slot groups x WW weight-row groups
     static constexpr int kThreads = kWaves * 64;
-    static_assert(BT % (32 * WT) == 0 && BT <= kBT, "slot tile height");
+    static_assert(BT % (32 * WT) == 0 && BT <= kMaxBT, "slot tile height");
     static constexpr int kTF = BT / WT / 32;                   // 32-slot MFMA tiles per wavefront
     static constexpr int kWF = 256 / WW / 32;                  // 32-row weight MFMA tiles per wavefront
     static constexpr int kTokStageRows = BT / kWaves;          // slot rows a wavefront stages
@@ -334,9 +335,11 @@ struct Gemm {
 #pragma unroll
             for (int i = 0; i < kTF; ++i) base_t[i] = (uint32_t)(trow[i] * kRowBytes + ((((trow[i] >> 1) & 7) ^ fhalf) << 4));
             constexpr int kM = kWF * kTF, kR = kWF + kTF;
-            static_assert(kLoadsTok == 4 && kLoadsPerOperand == 4 && kM == 8, "issue slots below");
+            constexpr int kL = kLoadsTok;       // loads per operand, wavefront and K step
+            constexpr int kLB = kL / 2;         // of them per k16 block (an operand's loads go out over two blocks)
+            static_assert(kLoadsPerOperand == kL && kL % 2 == 0 && kM % (2 * kLB) == 0, "issue slots below");
             bf16x8 tf[2][kTF], wf[2][kWF];
-            const uint32_t wave_off = (uint32_t)(wave * 32 * kRowBytes);   // both operands: 32 rows per wavefront
+            const uint32_t wave_off = (uint32_t)(wave * kStageRows * kRowBytes);   // both operands: the same rows per wavefront
             auto dma_deep = [&](int stage, int kt, int q) {
                 dma16(gp[kLoadsTok + q] + (size_t)kt * kRowBytes, lds0 + wave_off + (uint32_t)stage * 32768 + q * 1024);
             };
@@ -347,7 +350,7 @@ struct Gemm {
             // One k16 block: the MFMAs of fragment buffer mbuf, between them the reads of k16 step rks of
             // the current stages into buffer rbuf, and loads at the MFMA slots the schedule names.
             auto block = [&](auto mfma, int mbuf, auto read, int rks, int rbuf, uint32_t w_off, uint32_t t_off, auto shallow,
-                             bool dma, int dstage, int dkt, int q0, int n_loads) {
+                             bool dma, int dstage, int dkt, int q0) {
 #pragma unroll
                 for (int m = 0; m < kM; ++m) {
                     if (decltype(mfma)::value) {
@@ -363,10 +366,10 @@ struct Gemm {
                             tf[rbuf][m - kWF] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
                                 lds3 + (base_t[m - kWF] ^ (k_bits ^ t_off)));
                     }
-                    // n_loads == 2: slots 2 and 6; n_loads == 4: slots 0, 2, 4, 6
-                    const bool here = n_loads == 4 ? (m % 2 == 0) : (m == 2 || m == 6);
-                    if (dma && here) {
-                        const int q = q0 + (n_loads == 4 ? m / 2 : (m == 6 ? 1 : 0));
+                    // kLB loads per block, evenly spaced: after MFMA kM / (2 kLB) * (2 i + 1), i < kLB
+                    constexpr int kGap = kM / kLB;
+                    if (dma && m % kGap == kGap / 2) {
+                        const int q = q0 + m / kGap;
                         if (decltype(shallow)::value) dma_shallow(dstage, dkt, q);
                         else dma_deep(dstage, dkt, q);
                     }
@@ -377,18 +380,18 @@ struct Gemm {
             using No = std::false_type;
             // prologue: deep operand of K steps 0 and 1 and shallow operand of K step 0, in the order the waits below assume
 #pragma unroll
-            for (int q = 0; q < 4; ++q) dma_deep(0, 0, q);
+            for (int q = 0; q < kL; ++q) dma_deep(0, 0, q);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) dma_shallow(0, 0, q);
+            for (int q = 0; q < kL; ++q) dma_shallow(0, 0, q);
             if (KT > 1) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) dma_deep(1, 1, q);
+                for (int q = 0; q < kL; ++q) dma_deep(1, 1, q);
             }
             int ds = 0, ss = 0;  // deep stage (kt % 3) and shallow stage (kt % 2) of the K step being computed
             for (int kt = 0; kt < KT; ++kt) {
                 // Outstanding, oldest first: deep operand of K step kt, shallow operand of K step kt, deep operand of
                 // K step kt + 1 (requested during K step kt - 1 after that K step's shallow loads); the last may stay in flight.
-                if (kt + 1 < KT) wait_vmcnt<4>();
+                if (kt + 1 < KT) wait_vmcnt<kL>();
                 else wait_vmcnt<0>();
                 lds_barrier();
                 const uint32_t d_off = (uint32_t)ds * 32768, s_off = kShallowBase + (uint32_t)ss * 32768;
@@ -396,15 +399,15 @@ struct Gemm {
                 const bool more_s = kt + 1 < KT, more_d = kt + 2 < KT;
                 const int ds2 = ds == 0 ? 2 : ds - 1;  // stage of K step kt + 2 = the one K step kt - 1 used
                 // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
-                if (kt > 0) block(Yes{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0, 2);
-                else block(No{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0, 2);
-                block(Yes{}, 0, Yes{}, 1, 1, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 2, 2);
-                block(Yes{}, 1, Yes{}, 2, 0, w_off, t_off, No{}, more_d, ds2, kt + 2, 0, 2);
-                block(Yes{}, 0, Yes{}, 3, 1, w_off, t_off, No{}, more_d, ds2, kt + 2, 2, 2);
+                if (kt > 0) block(Yes{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0);
+                else block(No{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0);
+                block(Yes{}, 0, Yes{}, 1, 1, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, kLB);
+                block(Yes{}, 1, Yes{}, 2, 0, w_off, t_off, No{}, more_d, ds2, kt + 2, 0);
+                block(Yes{}, 0, Yes{}, 3, 1, w_off, t_off, No{}, more_d, ds2, kt + 2, kLB);
                 ds = ds == 2 ? 0 : ds + 1;
                 ss ^= 1;
             }
-            block(Yes{}, 1, No{}, 0, 0, 0u, 0u, No{}, false, 0, 0, 0, 2);
+            block(Yes{}, 1, No{}, 0, 0, 0u, 0u, No{}, false, 0, 0, 0);
         } else {
             // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
             // computed, and within a k16 step one at a time between MFMAs (see step() below).
@@ -417,7 +420,7 @@ struct Gemm {
             // SKIP: a wavefront whose 32 slot rows all lie past the tile's last slot stages no slot rows (the
             // fragments they would feed are skipped as well): a ragged tile then moves its weights plus only
             // its own slot rows through the load path, which is what bounds tiles of cold experts.
-            static_assert(32 % kTokStageRows == 0, "a wavefront stages rows of one 32-slot fragment");
+            static_assert(!SKIP || 32 % kTokStageRows == 0, "a wavefront stages rows of one 32-slot fragment");
             const bool stage_tok = !SKIP || (wave * kTokStageRows) / 32 * 32 < rows;  // its fragment has valid slots
             auto dma_one = [&](int stage, int kt, int l) {
                 if (SKIP && l < kLoadsTok && !stage_tok) return;
