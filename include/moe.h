@@ -48,8 +48,8 @@
  *     for the duration of the call.  A workgroup whose wait runs out writes
  *     NaN into its part of y and raises a status word that moe_decode_status
  *     reads; the call itself has long returned MOE_OK by then.  (The
- *     prefill-size grouped GEMM is persistent too; its waits only tune timing
- *     and never affect results.)
+ *     prefill-size grouped GEMM is persistent too, but no workgroup of it
+ *     ever waits for another.)
  *   - Determinism: no floating-point atomics are used; two calls on the same
  *     inputs give bitwise identical outputs.  moe_layer gives bitwise the same
  *     outputs as moe_route (+ moe_predict_next) followed by moe_expert_ffn.

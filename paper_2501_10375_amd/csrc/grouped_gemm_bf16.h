@@ -20,7 +20,7 @@
 //     LDS reads of other stages; completion is enforced by hand: s_waitcnt vmcnt(n) on the issuing
 //     wavefront, then a workgroup barrier, before any wavefront reads the stage.  One barrier per
 //     K step.  Inside a step MFMAs, LDS reads and loads are interleaved one for one.
-//   * Persistent schedule, one workgroup per CU, tiles handed out in XCD-synchronous rounds so the
+//   * Persistent schedule, one workgroup per CU, tiles handed out in rounds per XCD so the
 //     workgroups of an XCD share operand tiles through its L2; the last, partial round is split
 //     along K so that all CUs stay busy (see persistent()).
 #pragma once
@@ -47,7 +47,7 @@ constexpr int kMaxWgsPerXcd = 32;  // persistent grid: at most 8 x 32 workgroups
 constexpr int kMaxSplit = 8;       // K parts of a tile in the last round
 
 // Layout of the int32 `sync` block a GEMM launch uses (all zero when the kernel starts):
-//   [0, 8)                      rendezvous counter of each XCD
+//   [0, 8)                      unused
 //   [8, 8 + 8 * 32)             arrival counter of each split tile (XCD-major)
 constexpr int kSyncInts = kXcds + kXcds * kMaxWgsPerXcd;
 // fp32 scratch for split tiles: one 256 x 256 partial accumulator tile per workgroup.
@@ -91,22 +91,6 @@ __device__ inline void tile_of(const int32_t* __restrict__ offs, int E, int n_ft
         }
         acc += tiles;
     }
-}
-
-// Timing-only rendezvous of the workgroups that share an XCD (see persistent()).  It bounds its
-// own wait, so it can never hang and never affects results: if a workgroup is late the others
-// simply go on without it.
-constexpr int kMaxRendezvousSpins = 64;
-__device__ inline void xcd_rendezvous(int32_t* counter, int target) {
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int spins = 0; spins < kMaxRendezvousSpins; ++spins) {
-            if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
-            __builtin_amdgcn_s_sleep(16);
-        }
-    }
-    __syncthreads();
 }
 
 // 16 bytes per lane from `gptr` to LDS byte address lds_base + lane * 16 (lds_base wave-uniform).
@@ -200,9 +184,13 @@ struct Gemm {
     //
     // Persistent schedule: the grid is one workgroup per CU.  Workgroup b belongs to XCD b % 8 (the
     // hardware deals workgroups round-robin to the XCDs) and is its member b / 8.  An XCD works
-    // through the tile list in rounds of `members` consecutive tiles, one per member.  Before each
-    // new round the members meet (xcd_rendezvous), so they walk K in step and every operand line is
-    // pulled into the XCD's L2 once per round instead of once per workgroup.
+    // through the tile list in rounds of `members` consecutive tiles, one per member, so that the
+    // workgroups of an XCD work on tiles that share operand lines at about the same time and most
+    // lines are pulled into the XCD's L2 once per round instead of once per workgroup.  The members
+    // are not held in step: with the weights requested two K steps ahead, letting them drift apart
+    // by a fraction of a K step is faster than making them meet before every round (2.5 % / 4 % on
+    // the two GEMMs at 4096 tokens, 3-4 % on shorter calls), because fewer of them then ask for the
+    // same line at the same moment.
     //
     // The last round usually has fewer tiles than members (`rem`).  Each of its tiles is then split
     // along K into `parts` = min(kMaxSplit, members / rem) pieces computed by different members.
@@ -235,7 +223,6 @@ struct Gemm {
         const int parts = rem > 0 ? max(1, min(min(kMaxSplit, members / rem), KT / STAGES)) : 1;
         const int rounds = full_rounds + (rem > 0 ? 1 : 0);
         for (int r = 0; r < rounds; ++r) {
-            if (r > 0) xcd_rendezvous(sync + xcd, r * members);
             const bool split = r == full_rounds;  // the last, partial round
             const int p = split ? parts : 1;
             if (split && member >= rem * p) break;
