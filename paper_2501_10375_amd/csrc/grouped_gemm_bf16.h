@@ -47,7 +47,7 @@ constexpr int kMaxWgsPerXcd = 32;  // persistent grid: at most 8 x 32 workgroups
 constexpr int kMaxSplit = 8;       // K parts of a tile in the last round
 
 // Layout of the int32 `sync` block a GEMM launch uses (all zero when the kernel starts):
-//   [0, 8)                      unused
+//   [0, 8)                      tiles handed out so far in each XCD (see persistent())
 //   [8, 8 + 8 * 32)             arrival counter of each split tile (XCD-major)
 constexpr int kSyncInts = kXcds + kXcds * kMaxWgsPerXcd;
 // fp32 scratch for split tiles: one 256 x 256 partial accumulator tile per workgroup.
@@ -178,24 +178,27 @@ struct Gemm {
     static constexpr int kFragsPerMat = kWF / NMAT;
     static constexpr int kFeatPerWave = 32 * kFragsPerMat;
     static_assert(kLdsBytes >= 65536, "the epilogue transposes 64 KB through LDS");
+    // Start of the stage that a tile's prologue leaves alone (its first load arrives after the first barrier).
+    static constexpr int kHandoffOffset = W3 ? 3 * kTileBytes + kTokTileBytes : (STAGES - 1) * kStageBytes;
 
     // tok_base: gemm1 -> x [T, K] rows gathered via row_of_slot / topk; gemm2 -> act [A, K] rows = slots.
     // wa, wb: [E, N, K]; dst: gemm1 -> bf16 [A, N]; gemm2 -> fp32 [A, N].
     //
     // Persistent schedule: the grid is one workgroup per CU.  Workgroup b belongs to XCD b % 8 (the
     // hardware deals workgroups round-robin to the XCDs) and is its member b / 8.  An XCD works
-    // through the tile list in rounds of `members` consecutive tiles, one per member, so that the
-    // workgroups of an XCD work on tiles that share operand lines at about the same time and most
-    // lines are pulled into the XCD's L2 once per round instead of once per workgroup.  The members
-    // are not held in step: with the weights requested two K steps ahead, letting them drift apart
-    // by a fraction of a K step is faster than making them meet before every round (2.5 % / 4 % on
-    // the two GEMMs at 4096 tokens, 3-4 % on shorter calls), because fewer of them then ask for the
-    // same line at the same moment.
+    // through the tile list in rounds of `members` consecutive tiles, so that its workgroups work on
+    // tiles that share operand lines at about the same time and most lines are pulled into the
+    // XCD's L2 once per round instead of once per workgroup.  A workgroup starts with the tile of
+    // its member number and then takes the XCD's next tile from a counter whenever it has finished
+    // one: tiles differ in cost (ragged slot tiles skip the MFMAs of their empty fragments, tiles
+    // of cold experts wait for memory), and nobody waits for anybody.  Letting the members drift
+    // apart by a fraction of a K step is also faster than holding them in step, because fewer of
+    // them then ask for the same line at the same moment.
     //
     // The last round usually has fewer tiles than members (`rem`).  Each of its tiles is then split
-    // along K into `parts` = min(kMaxSplit, members / rem) pieces computed by different members.
-    // Every piece is written to `scratch` as a raw accumulator tile; the member that arrives last at
-    // the tile's counter adds the pieces in part order (so the result does not depend on who that
+    // along K into `parts` = min(kMaxSplit, members / rem) pieces handed out like tiles.
+    // Every piece is written to `scratch` as a raw accumulator tile; the workgroup that arrives last
+    // at the tile's counter adds the pieces in part order (so the result does not depend on who that
     // is) and runs the normal epilogue.
     static __device__ void persistent(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
                                       const uint16_t* __restrict__ wb, const int32_t* __restrict__ offs,
@@ -221,31 +224,35 @@ struct Gemm {
         const int rem = max(0, min(left, (xcd + 1) * chunk) - xcd * chunk);
         const int rem_first = full_rounds * per_super_round + xcd * chunk;
         const int parts = rem > 0 ? max(1, min(min(kMaxSplit, members / rem), KT / STAGES)) : 1;
-        const int rounds = full_rounds + (rem > 0 ? 1 : 0);
-        for (int r = 0; r < rounds; ++r) {
-            const bool split = r == full_rounds;  // the last, partial round
+        // Work items of this XCD in hand-out order: its whole tiles, then the pieces of its split tiles.
+        const int n_whole = full_rounds * members;
+        const int n_items = n_whole + rem * parts;
+        int item = member;  // the counter hands out items `members`, `members` + 1, ...
+        while (item < n_items) {
+            const bool split = item >= n_whole;
             const int p = split ? parts : 1;
-            if (split && member >= rem * p) break;
-            const int t = member / p, part = member - t * p;
-            const int tile_index = split ? rem_first + t : (r * kXcds + xcd) * members + t;
+            const int q = item - n_whole;  // piece number (split tiles only)
+            const int t = split ? q / p : item % members, part = split ? q - t * p : 0;
+            const int tile_index = split ? rem_first + t : ((item / members) * kXcds + xcd) * members + t;
             int e, slot0, rows, ft;
             tile_of(offs, E, n_ftiles, BT, tile_index, e, slot0, rows, ft);
             const int kt0 = (int)((long)KT * part / p), kt1 = (int)((long)KT * (part + 1) / p);
-            tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft, kt0, kt1, p, part,
-                 scratch + ((size_t)xcd * kMaxWgsPerXcd + (size_t)t * p) * kPartialFloats,
-                 sync + kXcds + xcd * kMaxWgsPerXcd + t, tok_alt, alt_mask);
+            item = members + tile(tok_base, wa, wb, row_of_slot, topk, N, K, dst, lds, e, slot0, rows, ft, kt0, kt1, p, part,
+                                  scratch + ((size_t)xcd * kMaxWgsPerXcd + (size_t)t * p) * kPartialFloats,
+                                  sync + kXcds + xcd * kMaxWgsPerXcd + t, sync + xcd, tok_alt, alt_mask);
         }
     }
 
     // One tile over K steps [kt_begin, kt_end).  parts == 1: a whole tile.  parts > 1: piece `part`
     // of a split tile; `partials` is where this tile's pieces live (piece p at p * kPartialFloats),
-    // `arrivals` its zero-initialised counter.
-    static __device__ void tile(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
+    // `arrivals` its zero-initialised counter.  Returns what `handed_out` (the XCD's count of items
+    // taken beyond every member's first) held when this workgroup asked for its next item.
+    static __device__ int tile(const uint16_t* __restrict__ tok_base, const uint16_t* __restrict__ wa,
                                 const uint16_t* __restrict__ wb, const int32_t* __restrict__ row_of_slot, int topk,
                                 int N, int K, void* __restrict__ dst, unsigned char* lds, int e, int slot0, int rows,
                                 int ft, int kt_begin, int kt_end, int parts, int part, float* __restrict__ partials,
-                                int32_t* __restrict__ arrivals, const uint16_t* __restrict__ tok_alt,
-                                const uint8_t* __restrict__ alt_mask) {
+                                int32_t* __restrict__ arrivals, int32_t* __restrict__ handed_out,
+                                const uint16_t* __restrict__ tok_alt, const uint8_t* __restrict__ alt_mask) {
         const int n0 = ft * kBF;
         const int tid = threadIdx.x, lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
@@ -487,7 +494,12 @@ struct Gemm {
             step(Yes{}, (kKSteps - 1) & 1, No{}, 0, 0, 0, false, 0, 0, kDmaParts);
         }
 
+        // Ask for the next work item now; the answer is needed only after the epilogue.
+        int next_item = 0;
+        if (tid == 0) next_item = __hip_atomic_fetch_add(handed_out, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
         // ---- split tiles: publish this piece; the last piece to arrive sums them all in part order.
+        bool finish = true;  // this workgroup writes the tile's result
         if (parts > 1) {
             float* mine = partials + (size_t)part * kPartialFloats;
             // The stores below are issued from inline asm, which the compiler's hazard bookkeeping does
@@ -514,9 +526,10 @@ struct Gemm {
             int* flag = reinterpret_cast<int*>(lds);
             if (tid == 0) *flag = __hip_atomic_fetch_add(arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
-            const bool is_last = *flag == parts - 1;
+            finish = __builtin_amdgcn_readfirstlane(*flag) == parts - 1;
             __syncthreads();  // everyone has read the flag before LDS is reused
-            if (!is_last) return;  // only ever in the last round, so nothing follows for this workgroup
+        }
+        if (finish && parts > 1) {
             // one wavefront drops whatever this CU's cache may hold of the pieces (an invalidate, no write-back)
             if (tid == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             __syncthreads();
@@ -547,7 +560,9 @@ struct Gemm {
         // 8 * (r / 4) + 4 * (lane / 32) + (r % 4), r = 0..15, i.e. 4 consecutive features per r / 4.
         // LDS rows are XOR-swizzled in 16-byte units so the row-wise read-back is conflict free.
         lds_barrier();  // every wavefront is done reading operand tiles; no load is outstanding
-        if (NMAT == 2) {
+        if (!finish) {
+            // another workgroup sums this tile's pieces
+        } else if (NMAT == 2) {
             // [256 slots][128 features] bf16, 256-byte rows, unit v of row r at position v ^ (r & 15)
 #pragma unroll
             for (int i = 0; i < kTF; ++i) {
@@ -606,6 +621,14 @@ struct Gemm {
                 }
             }
         }
+        // ---- hand the next item's number to every wavefront.  The first barrier also keeps the next
+        // tile's loads from landing in LDS that a slower wavefront is still reading back above; the word
+        // sits in the stage that no load is written to before the next tile's first barrier.
+        lds_barrier();
+        int* handoff = reinterpret_cast<int*>(lds + kHandoffOffset);
+        if (tid == 0) *handoff = next_item;
+        lds_barrier();
+        return __builtin_amdgcn_readfirstlane(*handoff);
     }
 };
 

@@ -32,7 +32,7 @@ constexpr int kTileTokensBf16 = 256;
 // and arrival flags.
 struct WorkspaceLayout {
     size_t dec_flags;    // uint32 [kDecodeFlagInts]  arrival flags, launch count and status word of the decode kernel's two grid-wide rendezvous
-    size_t sync;         // int32 [kSyncInts]    split-tile arrival counters of the two grouped GEMMs
+    size_t sync;         // int32 [kSyncInts]    tile hand-out and split-tile arrival counters of the two grouped GEMMs
     size_t hist;         // int32 [n_blocks, E]  per-block selection histogram
     size_t hist_next;    // int32 [n_blocks, E]  same for the next-layer gate
     size_t offs;         // int32 [E + 1]        exclusive scan of counts
@@ -83,8 +83,8 @@ hipError_t launch_hist_from_idx(const moe_shape_t& s, int tokens, const int32_t*
 // Sum block histograms into counts (counts may be null), and when
 // row_of_slot/slot_of are given build offs and the stable token->expert
 // permutation.
-// Counters and scratch of the persistent grouped GEMMs (see grouped_gemm_bf16.h): per launch 8 XCD
-// (unused) words + 8 x 32 split-tile arrival counters, and one 256 x 256 fp32 piece per workgroup.
+// Counters and scratch of the persistent grouped GEMMs (see grouped_gemm_bf16.h): per launch 8 tile
+// hand-out counters (one per XCD) + 8 x 32 split-tile arrival counters, and one 256 x 256 fp32 piece per workgroup.
 constexpr int kGemmSyncInts = 8 + 8 * 32;
 constexpr int kSyncInts = 2 * kGemmSyncInts;  // gemm1 and gemm2
 constexpr size_t kGemmScratchBytes = (size_t)8 * 32 * 256 * 256 * sizeof(float);
