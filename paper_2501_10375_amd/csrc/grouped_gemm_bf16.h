@@ -44,7 +44,7 @@ constexpr int kBT = 256;   // most slots per tile (the template parameter BT is 
 constexpr int kBW = 256;   // weight rows per tile (all matrices together)
 constexpr int kXcds = 8;
 constexpr int kMaxWgsPerXcd = 32;  // persistent grid: at most 8 x 32 workgroups
-constexpr int kMaxSplit = 8;       // K parts of a tile in the last round
+constexpr int kMaxSplit = 4;       // K parts of a tile in the last round (the sum of the pieces costs as much as 1/16 tile each)
 
 // Layout of the int32 `sync` block a GEMM launch uses (all zero when the kernel starts):
 //   [0, 8)                      tiles handed out so far in each XCD (see persistent())
@@ -328,10 +328,9 @@ struct Gemm {
             for (int j = 0; j < kWF; ++j) base_w[j] = (uint32_t)(wrow[j] * kRowBytes + ((((wrow[j] >> 1) & 7) ^ fhalf) << 4));
 #pragma unroll
             for (int i = 0; i < kTF; ++i) base_t[i] = (uint32_t)(trow[i] * kRowBytes + ((((trow[i] >> 1) & 7) ^ fhalf) << 4));
-            constexpr int kM = kWF * kTF, kR = kWF + kTF;
             constexpr int kL = kLoadsTok;       // loads per operand, wavefront and K step
             constexpr int kLB = kL / 2;         // of them per k16 block (an operand's loads go out over two blocks)
-            static_assert(kLoadsPerOperand == kL && kL % 2 == 0 && kM % (2 * kLB) == 0, "issue slots below");
+            static_assert(kLoadsPerOperand == kL && kL % 2 == 0, "issue slots below");
             bf16x8 tf[2][kTF], wf[2][kWF];
             const uint32_t wave_off = (uint32_t)(wave * kStageRows * kRowBytes);   // both operands: the same rows per wavefront
             auto dma_deep = [&](int stage, int kt, int q) {
@@ -341,67 +340,85 @@ struct Gemm {
                 dma16(gp[q] + (size_t)kt * kRowBytes,
                       lds0 + kShallowBase + wave_off + (uint32_t)stage * 32768 + q * 1024);
             };
-            // One k16 block: the MFMAs of fragment buffer mbuf, between them the reads of k16 step rks of
-            // the current stages into buffer rbuf, and loads at the MFMA slots the schedule names.
-            auto block = [&](auto mfma, int mbuf, auto read, int rks, int rbuf, uint32_t w_off, uint32_t t_off, auto shallow,
-                             bool dma, int dstage, int dkt, int q0) {
+            // In the first GEMM the main loop exists once per number of slot fragments with valid slots (TFE):
+            // a wavefront of a ragged tile issues only the MFMAs and fragment reads of those (its loads stay
+            // the same), finishes the tile sooner and the workgroup takes its next tile earlier.
+            auto main_loop = [&](auto tfe_c) {
+                constexpr int TFE = decltype(tfe_c)::value;
+                constexpr int kM = kWF * TFE, kR = kWF + TFE;
+                // One k16 block: the MFMAs of fragment buffer mbuf, between them the reads of k16 step rks of
+                // the current stages into buffer rbuf, and loads at the MFMA slots the schedule names.
+                auto block = [&](auto mfma, int mbuf, auto read, int rks, int rbuf, uint32_t w_off, uint32_t t_off, auto shallow,
+                                 bool dma, int dstage, int dkt, int q0) {
 #pragma unroll
-                for (int m = 0; m < kM; ++m) {
-                    if (decltype(mfma)::value) {
-                        const int i = m / kWF, j = m % kWF;
-                        acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
+                    for (int m = 0; m < (kM > kR ? kM : kR); ++m) {
+                        if (decltype(mfma)::value && m < kM) {
+                            const int i = m / kWF, j = m % kWF;
+                            acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[mbuf][j], tf[mbuf][i], acc[j][i], 0, 0, 0);
+                        }
+                        if (decltype(read)::value && m < kR) {
+                            const uint32_t k_bits = (uint32_t)(rks << 5);
+                            if (m < kWF)
+                                wf[rbuf][m] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
+                                    lds3 + (base_w[m] ^ (k_bits ^ w_off)));
+                            else
+                                tf[rbuf][m - kWF] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
+                                    lds3 + (base_t[m - kWF] ^ (k_bits ^ t_off)));
+                        }
+                        // kLB loads per block, evenly spaced over its MFMAs
+                        constexpr int kGap = kM / kLB;
+                        static_assert(kM % kLB == 0, "issue slots");
+                        if (dma && m < kM && m % kGap == kGap / 2) {
+                            const int q = q0 + m / kGap;
+                            if (decltype(shallow)::value) dma_shallow(dstage, dkt, q);
+                            else dma_deep(dstage, dkt, q);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    if (decltype(read)::value && m < kR) {
-                        const uint32_t k_bits = (uint32_t)(rks << 5);
-                        if (m < kWF)
-                            wf[rbuf][m] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
-                                lds3 + (base_w[m] ^ (k_bits ^ w_off)));
-                        else
-                            tf[rbuf][m - kWF] = *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>(
-                                lds3 + (base_t[m - kWF] ^ (k_bits ^ t_off)));
-                    }
-                    // kLB loads per block, evenly spaced: after MFMA kM / (2 kLB) * (2 i + 1), i < kLB
-                    constexpr int kGap = kM / kLB;
-                    if (dma && m % kGap == kGap / 2) {
-                        const int q = q0 + m / kGap;
-                        if (decltype(shallow)::value) dma_shallow(dstage, dkt, q);
-                        else dma_deep(dstage, dkt, q);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                };
+                using Yes = std::true_type;
+                using No = std::false_type;
+                // prologue: deep operand of K steps 0 and 1 and shallow operand of K step 0, in the order the waits below assume
+#pragma unroll
+                for (int q = 0; q < kL; ++q) dma_deep(0, 0, q);
+#pragma unroll
+                for (int q = 0; q < kL; ++q) dma_shallow(0, 0, q);
+                if (KT > 1) {
+#pragma unroll
+                    for (int q = 0; q < kL; ++q) dma_deep(1, 1, q);
                 }
+                int ds = 0, ss = 0;  // deep stage (kt % 3) and shallow stage (kt % 2) of the K step being computed
+                for (int kt = 0; kt < KT; ++kt) {
+                    // Outstanding, oldest first: deep operand of K step kt, shallow operand of K step kt, deep operand of
+                    // K step kt + 1 (requested during K step kt - 1 after that K step's shallow loads); the last may stay in flight.
+                    if (kt + 1 < KT) wait_vmcnt<kL>();
+                    else wait_vmcnt<0>();
+                    lds_barrier();
+                    const uint32_t d_off = (uint32_t)ds * 32768, s_off = kShallowBase + (uint32_t)ss * 32768;
+                    const uint32_t w_off = d_off, t_off = s_off;
+                    const bool more_s = kt + 1 < KT, more_d = kt + 2 < KT;
+                    const int ds2 = ds == 0 ? 2 : ds - 1;  // stage of K step kt + 2 = the one K step kt - 1 used
+                    // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
+                    if (kt > 0) block(Yes{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0);
+                    else block(No{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0);
+                    block(Yes{}, 0, Yes{}, 1, 1, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, kLB);
+                    block(Yes{}, 1, Yes{}, 2, 0, w_off, t_off, No{}, more_d, ds2, kt + 2, 0);
+                    block(Yes{}, 0, Yes{}, 3, 1, w_off, t_off, No{}, more_d, ds2, kt + 2, kLB);
+                    ds = ds == 2 ? 0 : ds + 1;
+                    ss ^= 1;
+                }
+                block(Yes{}, 1, No{}, 0, 0, 0u, 0u, No{}, false, 0, 0, 0);
             };
-            using Yes = std::true_type;
-            using No = std::false_type;
-            // prologue: deep operand of K steps 0 and 1 and shallow operand of K step 0, in the order the waits below assume
-#pragma unroll
-            for (int q = 0; q < kL; ++q) dma_deep(0, 0, q);
-#pragma unroll
-            for (int q = 0; q < kL; ++q) dma_shallow(0, 0, q);
-            if (KT > 1) {
-#pragma unroll
-                for (int q = 0; q < kL; ++q) dma_deep(1, 1, q);
+            if constexpr (NMAT == 2) {
+                switch (max(n_tf, 1)) {
+                    case 1: main_loop(std::integral_constant<int, 1>{}); break;
+                    case 2: main_loop(std::integral_constant<int, (kTF >= 2 ? 2 : kTF)>{}); break;
+                    case 3: main_loop(std::integral_constant<int, (kTF >= 3 ? 3 : kTF)>{}); break;
+                    default: main_loop(std::integral_constant<int, kTF>{}); break;
+                }
+            } else {
+                main_loop(std::integral_constant<int, kTF>{});  // measured: the second GEMM is slower with the shorter loops
             }
-            int ds = 0, ss = 0;  // deep stage (kt % 3) and shallow stage (kt % 2) of the K step being computed
-            for (int kt = 0; kt < KT; ++kt) {
-                // Outstanding, oldest first: deep operand of K step kt, shallow operand of K step kt, deep operand of
-                // K step kt + 1 (requested during K step kt - 1 after that K step's shallow loads); the last may stay in flight.
-                if (kt + 1 < KT) wait_vmcnt<kL>();
-                else wait_vmcnt<0>();
-                lds_barrier();
-                const uint32_t d_off = (uint32_t)ds * 32768, s_off = kShallowBase + (uint32_t)ss * 32768;
-                const uint32_t w_off = d_off, t_off = s_off;
-                const bool more_s = kt + 1 < KT, more_d = kt + 2 < KT;
-                const int ds2 = ds == 0 ? 2 : ds - 1;  // stage of K step kt + 2 = the one K step kt - 1 used
-                // last k16 step of K step kt - 1 (buffer 1) with the first reads of K step kt (buffer 0)
-                if (kt > 0) block(Yes{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0);
-                else block(No{}, 1, Yes{}, 0, 0, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, 0);
-                block(Yes{}, 0, Yes{}, 1, 1, w_off, t_off, Yes{}, more_s, ss ^ 1, kt + 1, kLB);
-                block(Yes{}, 1, Yes{}, 2, 0, w_off, t_off, No{}, more_d, ds2, kt + 2, 0);
-                block(Yes{}, 0, Yes{}, 3, 1, w_off, t_off, No{}, more_d, ds2, kt + 2, kLB);
-                ds = ds == 2 ? 0 : ds + 1;
-                ss ^= 1;
-            }
-            block(Yes{}, 1, No{}, 0, 0, 0u, 0u, No{}, false, 0, 0, 0);
         } else {
             // The loads of one stage are issued in kKSteps parts, one per k16 step of the K step being
             // computed, and within a k16 step one at a time between MFMAs (see step() below).

@@ -46,21 +46,42 @@ def test_bf16_prefill_path(oracle, T, H, F, E, k):
 
 
 @pytest.mark.parametrize("T,H,F,E,k", [
-    (1100, 256, 512, 2, 2),    # ~9 slot tiles of 256, everything in one split round (gemm1 2 K parts, gemm2 4)
+    (1100, 256, 512, 2, 2),    # ~9 slot tiles of 256, everything in one round whose tiles are split along K
     (700, 512, 384, 1, 1),     # one expert, top-1: a dense SwiGLU MLP; F = 3 feature tiles of gemm1
     (1300, 320, 448, 2, 2),    # F ends in a half feature tile, K = 5 steps of 64 (odd number of ring turns)
-    (2100, 1024, 320, 4, 2),   # 16 K steps: the two-stage ring wraps 8 times; ragged last slot tiles
+    (2100, 1024, 320, 4, 2),   # 16 K steps: the weight ring wraps 5 times; ragged last slot tiles
     (3000, 256, 2048, 2, 2),   # more tiles than compute units: one full round, then a split round
 ])
 def test_bf16_full_tile_flavour_every_token(oracle, T, H, F, E, k):
-    """Calls with at least 512 routed rows per expert take the branch-free GEMM flavour (256-slot
-    tiles, two LDS stages, no fragment skipping), the one long prefill calls run.  Narrow layers let
+    """Calls with at least 512 routed rows per expert run both GEMMs in the full-tile flavour (256-slot
+    tiles, three weight stages and two slot stages), the one long prefill calls run.  Narrow layers let
     the oracle check every token, so every wavefront's fragment rows and every epilogue position of
     the 256 x 256 tile is compared, including tiles whose K range is split between workgroups."""
     assert T * k >= E * 512
     d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16)
     r = check_layer(oracle, d, shape, res, torch.bfloat16, label=f"bf16 full tiles T={T}")
     print(r)
+    assert r["compared_tokens"] >= T - r["excluded"] - 2
+
+
+@pytest.mark.parametrize("T,H,F,E,k,seed", [
+    (200, 256, 256, 2, 2, 0),    # 200 rows per expert: gemm1 in the full-tile flavour, gemm2 in the ragged one
+    (150, 256, 384, 4, 4, 1),    # hot expert: a full slot tile and a short one; cold experts: one or two fragments
+    (330, 320, 448, 2, 2, 2),    # both GEMMs full-tile, second slot tile of every expert ragged
+    (140, 128, 640, 1, 1, 3),    # one expert with 140 rows: 5 valid fragments, 3 and 2 per wavefront group
+    (520, 192, 256, 8, 2, 4),    # 130 rows per expert on average: cold experts far below one fragment per group
+    (300, 256, 512, 2, 1, 5),    # top-1, about 150 rows per expert
+])
+def test_bf16_ragged_fragments_of_full_tiles_every_token(oracle, T, H, F, E, k, seed):
+    """From 128 routed rows per expert on gemm1 runs in the full-tile flavour, whose ragged slot tiles
+    issue only the MFMAs of their valid 32-slot fragments (a main loop per fragment count, chosen per
+    wavefront), while gemm2 stays in the ragged flavour below 320 rows per expert.  Every token is
+    compared, so every fragment count a wavefront can have (1 to 4) is exercised over these shapes."""
+    assert E * 128 <= T * k
+    d, shape, out, res = _run(T, H, F, E, k, torch.bfloat16, seed=seed)
+    counts = res["counts"].cpu().tolist()
+    r = check_layer(oracle, d, shape, res, torch.bfloat16, label=f"bf16 T={T} ragged fragments")
+    print(r, "rows per expert:", counts)
     assert r["compared_tokens"] >= T - r["excluded"] - 2
 
 
