@@ -820,6 +820,12 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
         }
     }
     __syncthreads();
+    if (!ROUTE && p.counts != nullptr && blockIdx.x == 0 && tid < p.E) {
+        // activation counts of selections made by a routing kernel before this one (17 to 32 tokens)
+        int c = p.accumulate ? p.counts[tid] : 0;
+        for (int a = 0; a < A; ++a) c += sm.idx[a] == tid;
+        p.counts[tid] = c;
+    }
     build_groups<NC>(sm.g, sm.idx, A, p.E);
     const uint32_t count = (uint32_t)__builtin_amdgcn_readfirstlane((int)last_count) + 1u;
     const uint32_t epoch = count ^ 0x9E3779B9u;
@@ -845,7 +851,7 @@ __global__ __launch_bounds__(kThreads) void decode_layer_kernel(DecodeArgs p) {
 hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
                                const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
                                const void* w2, void* y, void* act, uint32_t* flags, const StaleInput& alt,
-                               hipStream_t stream) {
+                               hipStream_t stream, int32_t* counts, int accumulate) {
     DecodeArgs p{};
     p.x_stale = static_cast<const uint16_t*>(alt.x_stale);
     p.stale = alt.stale;
@@ -863,6 +869,8 @@ hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, 
     } else {
         p.idx_in = topk_idx;
         p.w_in = topk_w;
+        p.counts = counts;
+        p.accumulate = accumulate;
     }
     p.w1 = static_cast<const uint16_t*>(w1);
     p.w3 = static_cast<const uint16_t*>(w3);

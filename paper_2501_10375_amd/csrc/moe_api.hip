@@ -190,9 +190,10 @@ hipError_t run_route(const moe_shape_t& s, int tokens, const void* x, GateArgs* 
     hipError_t e = launch_route(s, tokens, x, gates, n_gates, stream);
     stage_mark(stream, kStageRoute);
     if (e != hipSuccess) return e;
-    e = launch_finalize(s, tokens, ws.hist, gates[0].idx, counts, accumulate, permute ? ws.offs : nullptr,
-                        permute ? ws.row_of_slot : nullptr, permute ? ws.slot_of : nullptr,
-                        permute ? ws.sync : nullptr, stream);
+    if (counts != nullptr || permute)  // (a caller whose expert kernel counts the selections itself passes neither)
+        e = launch_finalize(s, tokens, ws.hist, gates[0].idx, counts, accumulate, permute ? ws.offs : nullptr,
+                            permute ? ws.row_of_slot : nullptr, permute ? ws.slot_of : nullptr,
+                            permute ? ws.sync : nullptr, stream);
     if (e != hipSuccess) return e;
     if (n_gates > 1 && counts_next != nullptr)
         e = launch_finalize(s, tokens, ws.hist_next, gates[1].idx, counts_next, 0, nullptr, nullptr, nullptr, nullptr, stream);
@@ -204,9 +205,10 @@ constexpr StaleInput kNoStaleInput = {nullptr, nullptr};
 
 hipError_t run_ffn(const moe_shape_t& s, int tokens, const void* x, const int32_t* idx, const float* w,
                    const void* w1, const void* w3, const void* w2, void* y, const Ws& ws, hipStream_t stream,
-                   const StaleInput& alt = kNoStaleInput) {
+                   const StaleInput& alt = kNoStaleInput, int32_t* counts = nullptr, int accumulate = 0) {
     if (stream_path(s, tokens))
-        return launch_decode_layer(s, tokens, x, nullptr, idx, w, w1, w3, w2, y, ws.act, ws.dec_flags, alt, stream);
+        return launch_decode_layer(s, tokens, x, nullptr, idx, w, w1, w3, w2, y, ws.act, ws.dec_flags, alt, stream, counts,
+                                   accumulate);
     if (s.dtype == MOE_F32)
         return launch_ffn_f32(s, tokens, static_cast<const float*>(x), w, static_cast<const float*>(w1),
                               static_cast<const float*>(w3), static_cast<const float*>(w2), static_cast<float*>(y),
@@ -263,10 +265,12 @@ int enqueue_layer(const moe_shape_t& s, int32_t tokens, const void* x, const voi
     }
     GateArgs g[2] = {{w_gate, gate_bias, topk_idx, topk_w, nullptr}, {w_gate_next, gate_bias_next, pred_idx, nullptr, nullptr}};
     const int n_gates = w_gate_next != nullptr ? 2 : 1;
-    hipError_t e = run_route(s, tokens, x, g, n_gates, counts, accumulate, nullptr, !stream_path(s, tokens), ws,
-                             stream);
+    // 17 to 32 tokens: the weight-streaming kernel needs no permutation and counts the selections itself.
+    const bool streaming = stream_path(s, tokens);
+    hipError_t e = run_route(s, tokens, x, g, n_gates, streaming ? nullptr : counts, accumulate, nullptr, !streaming, ws, stream);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    return dev(run_ffn(s, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream));
+    return dev(run_ffn(s, tokens, x, topk_idx, topk_w, w1, w3, w2, y, ws, stream, kNoStaleInput, streaming ? counts : nullptr,
+                       accumulate));
 }
 
 }  // namespace

@@ -148,9 +148,11 @@ struct DecodeRoute {
     const float* bias_next;
     int32_t* pred_idx;
 };
+// Without `route` the selections come in topk_idx / topk_w; `counts` (may be null) then receives their
+// histogram (added to what it holds with `accumulate`), written by the kernel's first workgroup.
 hipError_t launch_decode_layer(const moe_shape_t& s, int tokens, const void* x, const DecodeRoute* route,
                                const int32_t* topk_idx, const float* topk_w, const void* w1, const void* w3,
                                const void* w2, void* y, void* act, uint32_t* flags, const StaleInput& alt,
-                               hipStream_t stream);
+                               hipStream_t stream, int32_t* counts = nullptr, int accumulate = 0);
 
 }  // namespace moe

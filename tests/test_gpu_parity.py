@@ -312,6 +312,21 @@ def test_counts_accumulate_over_calls_and_zero_tokens(oracle):
     moe.run_layer(shape, d1, out, accumulate=True)
     torch.cuda.synchronize()
     assert out.counts.sum().item() == (40 * 2 + 3) * k
+    # 17 to 32 tokens: the weight-streaming kernel counts the selections of the routing kernel before it
+    d2 = dict(d)
+    d2["x"] = d["x"][:20].contiguous()
+    before = out.counts.clone()
+    r2 = moe.run_layer(shape, d2, out, accumulate=True)
+    torch.cuda.synchronize()
+    hist = torch.bincount(r2["idx"].flatten().long(), minlength=E).to(torch.int32)
+    assert torch.equal(out.counts, before + hist)
+    moe.run_layer(shape, d2, out, accumulate=False)
+    torch.cuda.synchronize()
+    assert torch.equal(out.counts, hist)
+    moe.run_layer(shape, d, out, accumulate=False)
+    moe.run_layer(shape, d, out, accumulate=True)
+    moe.run_layer(shape, d1, out, accumulate=True)
+    torch.cuda.synchronize()
     # zero tokens: counts untouched with accumulate, cleared without
     d0 = dict(d)
     d0["x"] = d["x"][:0]
